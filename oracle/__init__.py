@@ -1,0 +1,23 @@
+"""CPU oracle for the multi-ring allreduce (test infrastructure, not product code).
+
+Only tests, the smoke check and the benchmark's CPU-baseline leg may import this
+package.  It shares no code with the HIP library and never imports it.
+"""
+from .ddl_oracle import (  # noqa: F401
+    coords,
+    rank_of,
+    neighbour,
+    granule,
+    split,
+    level_segment,
+    fine_chunks,
+    schedule,
+    schedule_bytes,
+    allreduce_steps,
+    reduce_scatter_steps,
+    allgather_steps,
+    allreduce_fold,
+    sum_fp64,
+    ring_time_model,
+    multiring_time_model,
+)
