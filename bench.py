@@ -1,0 +1,180 @@
+#!/usr/bin/env python3
+"""Benchmark of the simulated multi-ring allreduce on one MI355X.
+
+A step is one whole allreduce (every reduce-scatter and all-gather phase of the schedule)
+over one set of P synthetic learner buffers that is already resident in HBM.  Prints ONE
+JSON line: allreduce GB/s per virtual learner (`value`), the HBM roofline of the dominant
+kernel measured with HIP events round every phase, and the CPU oracle timed on the host.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2] [--no-cpu]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=2, help="1-based index into the five configurations")
+    ap.add_argument("--sets-gib", type=float, default=96.0,
+                    help="HBM budget for distinct input sets (one per step until it is used up)")
+    ap.add_argument("--profile-passes", type=int, default=5)
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
+    args = ap.parse_args()
+
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build simulates the collective inside ONE GPU; "
+              "there is no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    import paper_1708_02188_amd as D
+    from paper_1708_02188_amd import inputs as I
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    dev = torch.device("cuda:0")
+    cfg = I.CONFIGS[args.config - 1]
+    P, dims, count, dist, seed = cfg["P"], cfg["dims"], cfg["count"], cfg["dist"], cfg["seed"]
+    K, W = args.steps, args.warmup
+    plan = D.ddl_ring_plan(dims, P, count)
+    D.ddl_plan_prepare(plan)
+    nsteps = D.ddl_plan_num_steps(plan)
+    bytes_total = D.ddl_plan_bytes_moved(plan)
+    resident = 4 * count * P
+
+    # Distinct, freshly seeded input sets, so repeated in-place sums neither overflow nor
+    # find the previous step's data in the caches.  If the budget is smaller than K+W sets
+    # the sets are reused round-robin (values grow by a factor P per reuse, timing is
+    # value-independent).
+    n_sets = max(1, min(K + W, int(args.sets_gib * 2 ** 30 // resident)))
+    stream = torch.cuda.current_stream()
+    sets = []
+    for s in range(n_sets):
+        bufs = [torch.empty(count, dtype=torch.float32, device=dev) for _ in range(P)]
+        for j, b in enumerate(bufs):
+            I.fill_device(b, seed + 1000 * s, j, dist, 0, stream)
+        sets.append(bufs)
+    torch.cuda.synchronize()
+
+    def run(i):
+        D.ddl_allreduce_sim(sets[i % n_sets], P, plan, count, D.DDL_F32, stream)
+
+    for i in range(W):
+        run(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(W, W + K):
+        run(i)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed * 1e3 / K
+    per_learner_gbs = 4 * count / (ms_per_step * 1e-3) / 1e9
+    hbm_gbs = bytes_total / (ms_per_step * 1e-3) / 1e9
+
+    # quick self-check on the last set used: every learner holds the same bits
+    last = sets[(W + K - 1) % n_sets]
+    same = all(torch.equal(last[0].view(torch.int32), last[j].view(torch.int32)) for j in range(1, P))
+
+    # Roofline of the dominant kernel (the reduce-add phase kernel carries 12 of every 20
+    # bytes): HIP events round every phase, on the stream the kernels run on.
+    kinds = [D.ddl_plan_get_step(plan, s)[0] for s in range(nsteps)]
+    step_bytes = [D.ddl_plan_step_bytes(plan, s) for s in range(nsteps)]
+    acc_ms = {D.DDL_STEP_REDUCE: 0.0, D.DDL_STEP_GATHER: 0.0}
+    acc_bytes = {D.DDL_STEP_REDUCE: 0, D.DDL_STEP_GATHER: 0}
+    launches = {D.DDL_STEP_REDUCE: 0, D.DDL_STEP_GATHER: 0}
+    per_step_ms = [0.0] * nsteps
+    for p in range(args.profile_passes):
+        for j, b in enumerate(sets[p % n_sets]):
+            I.fill_device(b, seed + 7777 + p, j, dist, 0, stream)
+        ms = D.ddl_allreduce_sim_profile(sets[p % n_sets], P, plan, count, D.DDL_F32, stream)
+        for s in range(nsteps):
+            if step_bytes[s]:
+                acc_ms[kinds[s]] += ms[s]
+                acc_bytes[kinds[s]] += step_bytes[s]
+                launches[kinds[s]] += 1
+                per_step_ms[s] += ms[s] / args.profile_passes
+
+    def kernel_line(kind, name):
+        if not launches[kind]:
+            return None
+        gbs = acc_bytes[kind] / (acc_ms[kind] * 1e-3) / 1e9
+        return {"kernel": name, "launches": launches[kind],
+                "avg_launch_us": 1e3 * acc_ms[kind] / launches[kind],
+                "avg_launch_bytes": acc_bytes[kind] / launches[kind],
+                "achieved_GBs": gbs, "frac": gbs / HBM_PEAK_GBS}
+
+    red = kernel_line(D.DDL_STEP_REDUCE, "reduce_add_step (step_kernel<float,true>)")
+    cpy = kernel_line(D.DDL_STEP_GATHER, "copy_step (step_kernel<float,false>)")
+    traffic = None
+    tfile = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tfile):
+        try:
+            traffic = json.load(open(tfile)).get(cfg["name"])
+        except (OSError, ValueError):
+            traffic = None
+    roofline = {"bound": "hbm", "kernel": red["kernel"] if red else None,
+                "achieved": red["achieved_GBs"] if red else None, "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": red["frac"] if red else None, "traffic": traffic,
+                "bytes_per_element": {"reduce_add_step": 12, "copy_step": 8},
+                "avg_launch_us": red["avg_launch_us"] if red else None,
+                "avg_launch_bytes": red["avg_launch_bytes"] if red else None,
+                "copy_step": cpy,
+                "whole_allreduce": {"achieved": hbm_gbs, "frac": hbm_gbs / HBM_PEAK_GBS,
+                                    "bytes": bytes_total},
+                "per_step_us": [round(1e3 * x, 2) for x in per_step_ms]}
+
+    del sets
+    torch.cuda.empty_cache()
+
+    cpu = None
+    if not args.no_cpu:
+        from oracle import allreduce_steps  # the CPU baseline leg: the oracle as it stands
+
+        c_count = count if resident <= 8 * 2 ** 30 else count // 16
+        V = [I.fill_host(c_count, seed, j, dist) for j in range(P)]
+        t0 = time.perf_counter()
+        allreduce_steps(V, dims)
+        c_s = time.perf_counter() - t0
+        cpu = {"value": 4 * c_count / c_s / 1e9, "unit": "GB/s per virtual learner", "cores": 1,
+               "kind": "oracle",
+               "sample": f"one pass of the numpy step simulator, P={P} dims={dims}, "
+                         f"{c_count} of {count} elements per learner, {c_s:.2f} s",
+               "hbm_equivalent_GBs": 20 * c_count * (P - 1) / c_s / 1e9,
+               "host_cores_available": os.cpu_count()}
+
+    out = {
+        "metric": "allreduce GB/s per virtual learner + achieved HBM GB/s (% of peak)",
+        "value": per_learner_gbs,
+        "unit": "GB/s per virtual learner",
+        "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": cfg["name"], "P": P, "dims": dims, "count": count, "dist": dist,
+                   "seed": seed, "phases": nsteps, "resident_bytes": resident,
+                   "input_sets": n_sets, "bus_GBs_per_learner": per_learner_gbs * 2 * (P - 1) / P},
+        "hbm_GBs": hbm_gbs, "hbm_frac_of_peak": hbm_gbs / HBM_PEAK_GBS,
+        "learners_identical": bool(same),
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+    if not same:
+        sys.exit(1)
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,168 @@
+/*
+ * libddlsim -- the multi-dimensional ring ("multi-ring") allreduce of gradient buffers,
+ * run as a simulated collective inside ONE gfx950 GPU: P virtual learners' buffers sit in
+ * that GPU's HBM and every phase of the schedule is executed by a HIP kernel.
+ *
+ * Plain C ABI: pointers and sizes only.  Where a pointer is a DEVICE pointer it says so;
+ * everything else is host memory.  `stream` arguments are a hipStream_t passed as void*
+ * (NULL = the default stream).
+ *
+ * Vocabulary (Sec. 4.3, "Topology aware communication"): N = P learners are placed in an
+ * m-dimensional box, P = d_1 * d_2 * ... * d_m; learner rank r has coordinates (c_1..c_m)
+ * with c_1 varying fastest (dimension 1 = fastest links).  A ring of d nodes reduces in
+ * d-1 phases; in each phase every node passes 1/d of the data to its +1 neighbour.  The
+ * reduce-scatter (Sec. 4.1 ReduceScatter) runs the rings of dimension 1, then 2, ... m,
+ * each on the part left over by the previous one; the all-gather (Sec. 4.1 AllGather)
+ * runs back through the dimensions m ... 1 and copies completed parts (Sec. 4.1
+ * assignment).  Afterwards every learner holds R = sum_j V_j (Sec. 4.3).
+ *
+ * A "step" is one phase: P independent operations, one per sending learner, each a
+ * contiguous element range [off, off+n) read from learner `src` and added into
+ * (reduce-scatter) or stored over (all-gather) the same range of learner `dst`.
+ *
+ * Chunk boundaries: a range of n elements is cut into ceil(n/G) granules of G = 16 /
+ * sizeof(element) elements; part k of d holds granules floor(k*ng/d) .. floor((k+1)*ng/d)-1.
+ * Every non-empty part therefore starts on a 16-byte boundary, only the part that ends
+ * the buffer can have a short granule, and parts may be empty for tiny buffers.
+ */
+#ifndef DDLSIM_H
+#define DDLSIM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Opaque schedule; created by ddl_ring_plan, owned by the library, freed by ddl_plan_free. */
+typedef struct ddl_plan ddl_plan_t;
+
+/* Element types.  Sums are formed in the element type itself, one rounding per addition
+ * (the paper speaks of "floating point entries" of 4 bytes: 90 M entries = 350 MB). */
+typedef enum {
+    DDL_F32 = 0,
+    DDL_F64 = 1,
+    DDL_I32 = 2
+} ddl_dtype_t;
+
+typedef enum {
+    DDL_OK = 0,
+    DDL_ERR_ARG = -1,           /* NULL pointer, P < 1, duplicate buffers, bad step index   */
+    DDL_ERR_DIMS = -2,          /* m < 1, a dimension < 1, or product of dims != P          */
+    DDL_ERR_DTYPE = -3,         /* unknown element type                                     */
+    DDL_ERR_ALIGN = -4,         /* a learner buffer is not 16-byte aligned                  */
+    DDL_ERR_PLAN_MISMATCH = -5, /* P / count / dtype differ from what the plan was made for */
+    DDL_ERR_NOMEM = -6,         /* host or device allocation failed                         */
+    DDL_ERR_HIP = -7            /* a HIP runtime call failed (no device, launch error, ...) */
+} ddl_status_t;
+
+enum { DDL_STEP_REDUCE = 0, DDL_STEP_GATHER = 1 };
+
+/* Largest supported number of learners and box dimensions. */
+#define DDL_MAX_LEARNERS 65535
+#define DDL_MAX_DIMS 16
+
+/*
+ * Build the schedule for a box dims[0..m-1] (Sec. 4.3: N = d_1*...*d_m) over P learners
+ * and `count` elements of `dtype` per learner.  Host-only: needs no GPU.  Dimensions of
+ * size 1 are allowed and contribute no steps; count == 0 is allowed.
+ * Returns NULL on error; *status (if not NULL) receives the code either way.
+ */
+ddl_plan_t* ddl_ring_plan(const int* dims, int m, int P, size_t count, ddl_dtype_t dtype,
+                          ddl_status_t* status);
+
+/* Free a plan and its device tables.  NULL is a no-op.  The caller must make sure no
+ * enqueued work still uses the plan (synchronise the streams first). */
+void ddl_plan_free(ddl_plan_t* plan);
+
+/*
+ * Copy the plan's step tables into device memory of the current device now, instead of
+ * at the first ddl_*_sim call that uses them (which otherwise allocates once).
+ */
+ddl_status_t ddl_plan_prepare(const ddl_plan_t* plan);
+
+/*
+ * In-place allreduce (Sec. 4.3: reduction R = sum_j V_j and its distribution to all
+ * learners) over the plan's schedule.
+ *   bufs   HOST array of P DEVICE pointers; bufs[j] is learner j's buffer of at least
+ *          `count` elements, 16-byte aligned, pairwise distinct and non-overlapping,
+ *          owned by the caller.  The array itself may be reused as soon as the call returns.
+ *   P, count, dtype must equal the plan's.
+ * Enqueues one kernel per step on `stream` and returns without synchronising; when the
+ * stream has drained, every bufs[j] holds the sum, bit-identical across learners, formed
+ * in the order the schedule fixes: within the ring of dimension t the partial sum of part
+ * k starts at ring position k+1 and is extended by positions k+2, ..., k+d_t (= k).
+ * A plan may be used from several streams at once only with disjoint buffers and P <= 256.
+ * Errors are reported before anything is enqueued, except DDL_ERR_HIP for a failed launch.
+ */
+ddl_status_t ddl_allreduce_sim(void** bufs, int P, const ddl_plan_t* plan, size_t count,
+                               ddl_dtype_t dtype, void* stream);
+
+/*
+ * The two halves as operations of their own (Sec. 4.1 ReduceScatter, AllGather); same
+ * arguments and rules as ddl_allreduce_sim.
+ * After ddl_reduce_scatter_sim learner r holds the completed sum on its own finest chunk
+ * (ddl_plan_owned_chunk) and partial sums elsewhere.  ddl_allgather_sim copies every
+ * learner's finest chunk into all learners and leaves the rest of the phases' ranges
+ * overwritten the same way.
+ */
+ddl_status_t ddl_reduce_scatter_sim(void** bufs, int P, const ddl_plan_t* plan, size_t count,
+                                    ddl_dtype_t dtype, void* stream);
+ddl_status_t ddl_allgather_sim(void** bufs, int P, const ddl_plan_t* plan, size_t count,
+                               ddl_dtype_t dtype, void* stream);
+
+/*
+ * ddl_allreduce_sim with a HIP event recorded on `stream` before and after every step's
+ * kernel.  SYNCHRONISES the stream before returning.  step_ms (host, ddl_plan_num_steps
+ * floats) receives each step's elapsed milliseconds (0 for a step that moves nothing).
+ * Meant for measurement; the events add a little time between kernels.
+ */
+ddl_status_t ddl_allreduce_sim_profile(void** bufs, int P, const ddl_plan_t* plan, size_t count,
+                                       ddl_dtype_t dtype, void* stream, float* step_ms);
+
+/* ---- plan introspection (host only) ------------------------------------------------ */
+
+/* 2 * sum_t (d_t - 1): Sec. 4.3, d-1 phases per ring, once reducing and once gathering.
+ * Returns -1 for a NULL plan. */
+int ddl_plan_num_steps(const ddl_plan_t* plan);
+
+/* Learners P of the plan (0 for NULL). */
+int ddl_plan_num_learners(const ddl_plan_t* plan);
+
+/* Bytes the whole schedule moves through memory: 3 accesses per element of a reduce
+ * operation (read src, read dst, write dst), 2 per element of a gather operation.
+ * Equals 5 * sizeof(element) * count * (P - 1) when count is a multiple of G * P. */
+size_t ddl_plan_bytes_moved(const ddl_plan_t* plan);
+
+/* The same for one step; 0 for a bad index. */
+size_t ddl_plan_step_bytes(const ddl_plan_t* plan, int step);
+
+/*
+ * Describe step `step` (0-based).  *kind = DDL_STEP_REDUCE / DDL_STEP_GATHER, *dim = the
+ * 0-based box dimension whose rings run; src/dst/off/n are caller arrays of P entries
+ * (any may be NULL), filled in order of the sending learner: operation i reads
+ * [off[i], off[i]+n[i]) of learner src[i] = i and targets the same range of dst[i].
+ */
+ddl_status_t ddl_plan_get_step(const ddl_plan_t* plan, int step, int* kind, int* dim,
+                               int* src, int* dst, size_t* off, size_t* n);
+
+/* The finest chunk learner `learner` owns after the reduce-scatter: [*off, *off + *n). */
+ddl_status_t ddl_plan_owned_chunk(const ddl_plan_t* plan, int learner, size_t* off, size_t* n);
+
+/*
+ * Estimated time on a cluster, seconds (Sec. 4.3: T ~ sum_{j=1}^{d-1} (S/(d*B) + L) per
+ * ring): dimension t runs a ring of d_t nodes over the bytes left at its level with
+ * bandwidth bw[t] (bytes/s) and per-phase latency lat[t] (s); charged once for the
+ * reduction and once for the distribution.  bw, lat: host arrays of m doubles.
+ * Returns a negative value on bad arguments.
+ */
+double ddl_plan_model_time(const ddl_plan_t* plan, const double* bw, const double* lat);
+
+/* Static, human-readable name of a status code. */
+const char* ddl_status_string(ddl_status_t status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DDLSIM_H */

@@ -17,6 +17,7 @@ from .ddl_oracle import (  # noqa: F401
     reduce_scatter_steps,
     allgather_steps,
     allreduce_fold,
+    allreduce_fold_range,
     sum_fp64,
     ring_time_model,
     multiring_time_model,

@@ -230,23 +230,24 @@ def allgather_steps(V, dims) -> list:
     return _run(bufs, steps)
 
 
-def allreduce_fold(V, dims) -> np.ndarray:
-    """Form (ii): the same result element by element, without simulating phases.
+def allreduce_fold_range(get, dims, count: int, lo: int, hi: int, dtype) -> np.ndarray:
+    """Form (ii): the result on elements [lo, hi) only, element by element, without
+    simulating phases.  `get(r, a, b)` returns elements [a, b) of learner r's input.
 
     For an element of finest chunk k = (k_1..k_m), the ring of dimension t adds the
     d_t partial results in the order of ring positions k_t+1, k_t+2, ..., k_t+d_t
     (mod d_t), left to right: the partial sum starts at the position after the
     chunk's owner and travels once round the ring until it reaches the owner.
     Dimension 1 is folded first, then dimension 2 over those results, and so on.
-    Returns the single vector every learner ends with.
     """
-    _, count = _check_inputs(V, dims)
-    dtype = V[0].dtype
     m = len(dims)
-    out = np.empty(count, dtype=dtype)
-    for k, a, b in fine_chunks(dims, count, granule(dtype)):
+    out = np.empty(hi - lo, dtype=dtype)
+    for k, ca, cb in fine_chunks(dims, count, granule(dtype)):
+        a, b = max(ca, lo), min(cb, hi)
+        if a >= b:
+            continue
         # A maps the not-yet-folded coordinates (c_t..c_m) to a partial result
-        A = {c: V[rank_of(c, dims)][a:b] for c in itertools.product(*[range(d) for d in dims])}
+        A = {c: get(rank_of(c, dims), a, b) for c in itertools.product(*[range(d) for d in dims])}
         for t in range(m):
             d = dims[t]
             nxt = {}
@@ -256,8 +257,14 @@ def allreduce_fold(V, dims) -> np.ndarray:
                     acc = acc + A[((k[t] + i) % d,) + rest]
                 nxt[rest] = acc
             A = nxt
-        out[a:b] = A[()]
+        out[a - lo:b - lo] = A[()]
     return out
+
+
+def allreduce_fold(V, dims) -> np.ndarray:
+    """Form (ii) over whole in-memory buffers: the single vector every learner ends with."""
+    _, count = _check_inputs(V, dims)
+    return allreduce_fold_range(lambda r, a, b: V[r][a:b], dims, count, 0, count, V[0].dtype)
 
 
 def sum_fp64(V) -> np.ndarray:

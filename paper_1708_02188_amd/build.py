@@ -1,0 +1,58 @@
+"""Compile the in-tree HIP libraries for gfx950 with hipcc (cross-compiles without a GPU).
+
+    python -m paper_1708_02188_amd.build        # builds libddlsim.so and libddlgen.so
+
+Extra -D options (kernel tuning knobs of csrc/kernels.hip) can be given via the
+environment variable DDLSIM_CXXFLAGS, and another output directory via DDLSIM_OUT.
+"""
+import os
+import shlex
+import subprocess
+import sys
+
+PKG = os.path.dirname(os.path.abspath(__file__))
+CSRC = os.path.join(PKG, "csrc")
+
+COMMON = [
+    "--offload-arch=gfx950",
+    "-O3",
+    "-std=c++17",
+    "-fPIC",
+    "-shared",
+    "-Wall",
+    # packed fp32 instructions are kept out of every kernel (one rounding per scalar add)
+    "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    "-ffp-contract=off",
+]
+
+LIBS = {
+    "libddlsim.so": ["plan.cpp", "api.cpp", "kernels.hip"],
+    "libddlgen.so": ["ddlgen.hip"],
+}
+
+
+def hipcc():
+    for cand in (os.environ.get("HIPCC"), "/opt/rocm/bin/hipcc", "hipcc"):
+        if cand and (os.path.sep not in cand or os.path.exists(cand)):
+            return cand
+    raise RuntimeError("hipcc not found")
+
+
+def build_all(out_dir=None, extra_flags=None, verbose=True):
+    out_dir = out_dir or os.environ.get("DDLSIM_OUT") or PKG
+    extra = list(extra_flags or []) + shlex.split(os.environ.get("DDLSIM_CXXFLAGS", ""))
+    os.makedirs(out_dir, exist_ok=True)
+    built = []
+    for lib, sources in LIBS.items():
+        out = os.path.join(out_dir, lib)
+        cmd = [hipcc()] + COMMON + extra + ["-o", out] + [os.path.join(CSRC, s) for s in sources]
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        subprocess.run(cmd, check=True)
+        built.append(out)
+    return built
+
+
+if __name__ == "__main__":
+    build_all()
+    sys.exit(0)

@@ -1,0 +1,267 @@
+// C ABI of libddlsim (declared in include/ddlsim.h): argument checks, device tables,
+// and the per-step launches.  No element arithmetic happens on the host.
+#include <hip/hip_runtime_api.h>
+
+#include <algorithm>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "kernels.h"
+#include "plan.h"
+
+namespace {
+
+using ddl::DeviceTables;
+using ddl::Op;
+using ddl::PtrTable;
+
+void set_status(ddl_status_t* status, ddl_status_t value) {
+    if (status) *status = value;
+}
+
+// Device copies of the step tables for the current device, created on first use.
+ddl_status_t device_tables(const ddl_plan* plan, DeviceTables* out) {
+    int device = -1;
+    if (hipGetDevice(&device) != hipSuccess) return DDL_ERR_HIP;
+    std::lock_guard<std::mutex> lock(plan->mu);
+    for (const DeviceTables& t : plan->tables)
+        if (t.device == device) {
+            *out = t;
+            return DDL_OK;
+        }
+    DeviceTables t;
+    t.device = device;
+    const size_t ops_bytes = plan->ops.size() * sizeof(Op);
+    if (ops_bytes) {
+        if (hipMalloc(reinterpret_cast<void**>(&t.ops), ops_bytes) != hipSuccess) return DDL_ERR_NOMEM;
+        if (hipMemcpy(t.ops, plan->ops.data(), ops_bytes, hipMemcpyHostToDevice) != hipSuccess) {
+            (void)hipFree(t.ops);
+            return DDL_ERR_HIP;
+        }
+    }
+    if (plan->P > ddl::kKernargLearners) {
+        if (hipMalloc(reinterpret_cast<void**>(&t.ptrs), size_t(plan->P) * sizeof(void*)) != hipSuccess) {
+            if (t.ops) (void)hipFree(t.ops);
+            return DDL_ERR_NOMEM;
+        }
+    }
+    plan->tables.push_back(t);
+    *out = t;
+    return DDL_OK;
+}
+
+ddl_status_t check_call(void** bufs, int P, const ddl_plan* plan, size_t count, ddl_dtype_t dtype) {
+    if (plan == nullptr || bufs == nullptr || P < 1) return DDL_ERR_ARG;
+    if (ddl::dtype_size(dtype) == 0) return DDL_ERR_DTYPE;
+    if (P != plan->P || count != plan->count || dtype != plan->dtype) return DDL_ERR_PLAN_MISMATCH;
+    for (int j = 0; j < P; ++j) {
+        if (bufs[j] == nullptr) return DDL_ERR_ARG;
+        if (reinterpret_cast<uintptr_t>(bufs[j]) % 16 != 0) return DDL_ERR_ALIGN;
+    }
+    // learners must not share memory: sorted by address, each buffer must end before the next
+    std::vector<uintptr_t> sorted(P);
+    for (int j = 0; j < P; ++j) sorted[j] = reinterpret_cast<uintptr_t>(bufs[j]);
+    std::sort(sorted.begin(), sorted.end());
+    const uintptr_t bytes = uintptr_t(count) * uintptr_t(plan->elem_size);
+    for (int j = 0; j + 1 < P; ++j) {
+        if (sorted[j] == sorted[j + 1]) return DDL_ERR_ARG;
+        if (sorted[j] + bytes > sorted[j + 1]) return DDL_ERR_ARG;
+    }
+    return DDL_OK;
+}
+
+// Run steps [first, last) of the plan.  events: NULL, or last-first+1 created events that
+// are recorded round every launch.
+ddl_status_t run_steps(void** bufs, int P, const ddl_plan* plan, size_t count, ddl_dtype_t dtype,
+                       void* stream_v, int first, int last, hipEvent_t* events) {
+    ddl_status_t st = check_call(bufs, P, plan, count, dtype);
+    if (st != DDL_OK) return st;
+    hipStream_t stream = static_cast<hipStream_t>(stream_v);
+    if (first >= last || count == 0) return DDL_OK;
+
+    DeviceTables tables;
+    st = device_tables(plan, &tables);
+    if (st != DDL_OK) return st;
+
+    PtrTable table;
+    void* const* d_ptrs = nullptr;
+    if (P <= ddl::kKernargLearners) {
+        std::memset(&table, 0, sizeof(table));
+        std::memcpy(table.p, bufs, size_t(P) * sizeof(void*));
+    } else {
+        // pageable source: the runtime has copied the array out before this returns
+        if (hipMemcpyAsync(tables.ptrs, bufs, size_t(P) * sizeof(void*), hipMemcpyHostToDevice,
+                           stream) != hipSuccess)
+            return DDL_ERR_HIP;
+        d_ptrs = tables.ptrs;
+    }
+    if (events && hipEventRecord(events[0], stream) != hipSuccess) return DDL_ERR_HIP;
+    for (int s = first; s < last; ++s) {
+        if (ddl::launch_step(*plan, plan->steps[s], tables.ops + size_t(s) * P, table, d_ptrs,
+                             stream) != hipSuccess)
+            return DDL_ERR_HIP;
+        if (events && hipEventRecord(events[s - first + 1], stream) != hipSuccess) return DDL_ERR_HIP;
+    }
+    return DDL_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+ddl_plan_t* ddl_ring_plan(const int* dims, int m, int P, size_t count, ddl_dtype_t dtype,
+                          ddl_status_t* status) {
+    const int elem = ddl::dtype_size(dtype);
+    if (elem == 0) {
+        set_status(status, DDL_ERR_DTYPE);
+        return nullptr;
+    }
+    ddl_status_t st = ddl::validate_dims(dims, m, P);
+    if (st == DDL_OK && count > (uint64_t(1) << 56)) st = DDL_ERR_ARG;
+    if (st != DDL_OK) {
+        set_status(status, st);
+        return nullptr;
+    }
+    ddl_plan* plan = nullptr;
+    try {
+        plan = new ddl_plan;
+        plan->dims.assign(dims, dims + m);
+        plan->P = P;
+        plan->count = count;
+        plan->dtype = dtype;
+        plan->elem_size = elem;
+        ddl::build_schedule(plan);
+    } catch (const std::bad_alloc&) {
+        delete plan;
+        set_status(status, DDL_ERR_NOMEM);
+        return nullptr;
+    }
+    set_status(status, DDL_OK);
+    return plan;
+}
+
+void ddl_plan_free(ddl_plan_t* plan) {
+    if (plan == nullptr) return;
+    for (const DeviceTables& t : plan->tables) {
+        if (t.ops) (void)hipFree(t.ops);
+        if (t.ptrs) (void)hipFree(t.ptrs);
+    }
+    delete plan;
+}
+
+ddl_status_t ddl_plan_prepare(const ddl_plan_t* plan) {
+    if (plan == nullptr) return DDL_ERR_ARG;
+    DeviceTables t;
+    return device_tables(plan, &t);
+}
+
+ddl_status_t ddl_allreduce_sim(void** bufs, int P, const ddl_plan_t* plan, size_t count,
+                               ddl_dtype_t dtype, void* stream) {
+    const int steps = plan ? static_cast<int>(plan->steps.size()) : 0;
+    return run_steps(bufs, P, plan, count, dtype, stream, 0, steps, nullptr);
+}
+
+ddl_status_t ddl_reduce_scatter_sim(void** bufs, int P, const ddl_plan_t* plan, size_t count,
+                                    ddl_dtype_t dtype, void* stream) {
+    const int split = plan ? plan->first_gather : 0;
+    return run_steps(bufs, P, plan, count, dtype, stream, 0, split, nullptr);
+}
+
+ddl_status_t ddl_allgather_sim(void** bufs, int P, const ddl_plan_t* plan, size_t count,
+                               ddl_dtype_t dtype, void* stream) {
+    const int split = plan ? plan->first_gather : 0;
+    const int steps = plan ? static_cast<int>(plan->steps.size()) : 0;
+    return run_steps(bufs, P, plan, count, dtype, stream, split, steps, nullptr);
+}
+
+ddl_status_t ddl_allreduce_sim_profile(void** bufs, int P, const ddl_plan_t* plan, size_t count,
+                                       ddl_dtype_t dtype, void* stream, float* step_ms) {
+    if (step_ms == nullptr) return DDL_ERR_ARG;
+    ddl_status_t st = check_call(bufs, P, plan, count, dtype);
+    if (st != DDL_OK) return st;
+    const int steps = static_cast<int>(plan->steps.size());
+    for (int s = 0; s < steps; ++s) step_ms[s] = 0.0f;
+    if (steps == 0 || count == 0) return DDL_OK;
+    std::vector<hipEvent_t> events(steps + 1, nullptr);
+    st = DDL_OK;
+    for (int i = 0; i <= steps && st == DDL_OK; ++i)
+        if (hipEventCreate(&events[i]) != hipSuccess) st = DDL_ERR_HIP;
+    if (st == DDL_OK) st = run_steps(bufs, P, plan, count, dtype, stream, 0, steps, events.data());
+    if (hipStreamSynchronize(static_cast<hipStream_t>(stream)) != hipSuccess && st == DDL_OK)
+        st = DDL_ERR_HIP;
+    if (st == DDL_OK)
+        for (int s = 0; s < steps; ++s)
+            if (plan->steps[s].max_n != 0 &&
+                hipEventElapsedTime(&step_ms[s], events[s], events[s + 1]) != hipSuccess)
+                st = DDL_ERR_HIP;
+    for (hipEvent_t e : events)
+        if (e) (void)hipEventDestroy(e);
+    return st;
+}
+
+int ddl_plan_num_steps(const ddl_plan_t* plan) {
+    return plan ? static_cast<int>(plan->steps.size()) : -1;
+}
+
+int ddl_plan_num_learners(const ddl_plan_t* plan) { return plan ? plan->P : 0; }
+
+size_t ddl_plan_bytes_moved(const ddl_plan_t* plan) { return plan ? plan->bytes_total : 0; }
+
+size_t ddl_plan_step_bytes(const ddl_plan_t* plan, int step) {
+    if (plan == nullptr || step < 0 || step >= static_cast<int>(plan->steps.size())) return 0;
+    return plan->steps[step].bytes;
+}
+
+ddl_status_t ddl_plan_get_step(const ddl_plan_t* plan, int step, int* kind, int* dim, int* src,
+                               int* dst, size_t* off, size_t* n) {
+    if (plan == nullptr || step < 0 || step >= static_cast<int>(plan->steps.size()))
+        return DDL_ERR_ARG;
+    const ddl::Step& st = plan->steps[step];
+    if (kind) *kind = st.kind;
+    if (dim) *dim = st.dim;
+    const Op* ops = plan->ops.data() + size_t(step) * plan->P;
+    for (int i = 0; i < plan->P; ++i) {
+        if (src) src[i] = ops[i].src;
+        if (dst) dst[i] = ops[i].dst;
+        if (off) off[i] = ops[i].off;
+        if (n) n[i] = ops[i].n;
+    }
+    return DDL_OK;
+}
+
+ddl_status_t ddl_plan_owned_chunk(const ddl_plan_t* plan, int learner, size_t* off, size_t* n) {
+    if (plan == nullptr || learner < 0 || learner >= plan->P) return DDL_ERR_ARG;
+    if (off) *off = plan->own_off[learner];
+    if (n) *n = plan->own_n[learner];
+    return DDL_OK;
+}
+
+double ddl_plan_model_time(const ddl_plan_t* plan, const double* bw, const double* lat) {
+    if (plan == nullptr || bw == nullptr || lat == nullptr) return -1.0;
+    double level_bytes = double(plan->count) * plan->elem_size;
+    double total = 0.0;
+    for (size_t t = 0; t < plan->dims.size(); ++t) {
+        const int d = plan->dims[t];
+        if (!(bw[t] > 0.0) || lat[t] < 0.0) return -1.0;
+        total += 2.0 * (d - 1) * (level_bytes / (d * bw[t]) + lat[t]);
+        level_bytes /= d;
+    }
+    return total;
+}
+
+const char* ddl_status_string(ddl_status_t status) {
+    switch (status) {
+        case DDL_OK: return "ok";
+        case DDL_ERR_ARG: return "invalid argument";
+        case DDL_ERR_DIMS: return "box dimensions do not describe the learners";
+        case DDL_ERR_DTYPE: return "unknown element type";
+        case DDL_ERR_ALIGN: return "learner buffer is not 16-byte aligned";
+        case DDL_ERR_PLAN_MISMATCH: return "arguments differ from the plan's";
+        case DDL_ERR_NOMEM: return "out of memory";
+        case DDL_ERR_HIP: return "HIP runtime error";
+    }
+    return "unknown status";
+}
+
+}  // extern "C"

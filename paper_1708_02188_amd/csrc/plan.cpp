@@ -1,0 +1,94 @@
+// Schedule planner: Sec. 4.3 (ring of d nodes = d-1 phases of d concurrent transfers of
+// 1/d of the data; learners in an m-dimensional box, P = d_1*...*d_m), with the
+// reduce-scatter taking dimensions 1..m and the all-gather m..1 (Sec. 4.1 operations).
+#include "plan.h"
+
+namespace ddl {
+
+int dtype_size(ddl_dtype_t dtype) {
+    switch (dtype) {
+        case DDL_F32: return 4;
+        case DDL_F64: return 8;
+        case DDL_I32: return 4;
+    }
+    return 0;
+}
+
+ddl_status_t validate_dims(const int* dims, int m, int P) {
+    if (P < 1 || P > DDL_MAX_LEARNERS) return DDL_ERR_ARG;
+    if (dims == nullptr) return DDL_ERR_ARG;
+    if (m < 1 || m > DDL_MAX_DIMS) return DDL_ERR_DIMS;
+    int64_t prod = 1;
+    for (int t = 0; t < m; ++t) {
+        if (dims[t] < 1) return DDL_ERR_DIMS;
+        prod *= dims[t];
+        if (prod > DDL_MAX_LEARNERS) return DDL_ERR_DIMS;
+    }
+    return prod == P ? DDL_OK : DDL_ERR_DIMS;
+}
+
+void split_range(uint64_t lo, uint64_t hi, uint64_t d, uint64_t k, uint64_t G,
+                 uint64_t* a, uint64_t* b) {
+    const uint64_t n = hi - lo;
+    const uint64_t granules = (n + G - 1) / G;
+    // d <= 65536 and granules < 2^60: the products cannot overflow
+    uint64_t first = (k * granules / d) * G;
+    uint64_t last = ((k + 1) * granules / d) * G;
+    *a = lo + (first < n ? first : n);
+    *b = lo + (last < n ? last : n);
+}
+
+void build_schedule(ddl_plan* plan) {
+    const int m = static_cast<int>(plan->dims.size());
+    const int P = plan->P;
+    const uint64_t G = 16 / static_cast<uint64_t>(plan->elem_size);
+
+    // Segment every learner works on at the start of each dimension (level 0 = everything).
+    std::vector<std::vector<uint64_t>> lo(m + 1, std::vector<uint64_t>(P, 0));
+    std::vector<std::vector<uint64_t>> hi(m + 1, std::vector<uint64_t>(P, plan->count));
+    std::vector<int> stride(m + 1, 1);  // rank distance of one position along dimension t
+    for (int t = 0; t < m; ++t) {
+        const int d = plan->dims[t];
+        stride[t + 1] = stride[t] * d;
+        for (int r = 0; r < P; ++r) {
+            const int pos = (r / stride[t]) % d;
+            split_range(lo[t][r], hi[t][r], d, pos, G, &lo[t + 1][r], &hi[t + 1][r]);
+        }
+    }
+    plan->own_off.assign(lo[m].begin(), lo[m].end());
+    plan->own_n.resize(P);
+    for (int r = 0; r < P; ++r) plan->own_n[r] = hi[m][r] - lo[m][r];
+
+    auto emit = [&](int kind, int t, int phase) {
+        const int d = plan->dims[t];
+        Step st{kind, t, 0, 0};
+        const uint64_t per_elem = (kind == DDL_STEP_REDUCE ? 3u : 2u) * plan->elem_size;
+        for (int r = 0; r < P; ++r) {
+            const int pos = (r / stride[t]) % d;
+            const int next = r + ((pos + 1) % d - pos) * stride[t];
+            // reduce: in phase s ring position c passes on part c-s-1, the partial sum that
+            // set out one position after the part's owner; gather: position c passes on
+            // part c-s, its own completed part first.
+            const int back = (kind == DDL_STEP_REDUCE) ? phase + 1 : phase;
+            const int part = ((pos - back) % d + d) % d;
+            Op op;
+            split_range(lo[t][r], hi[t][r], d, part, G, &op.off, &op.n);
+            op.n -= op.off;
+            op.src = r;
+            op.dst = next;
+            if (op.n > st.max_n) st.max_n = op.n;
+            st.bytes += op.n * per_elem;
+            plan->ops.push_back(op);
+        }
+        plan->bytes_total += st.bytes;
+        plan->steps.push_back(st);
+    };
+
+    for (int t = 0; t < m; ++t)
+        for (int phase = 0; phase + 1 < plan->dims[t]; ++phase) emit(DDL_STEP_REDUCE, t, phase);
+    plan->first_gather = static_cast<int>(plan->steps.size());
+    for (int t = m - 1; t >= 0; --t)
+        for (int phase = 0; phase + 1 < plan->dims[t]; ++phase) emit(DDL_STEP_GATHER, t, phase);
+}
+
+}  // namespace ddl

@@ -1,0 +1,68 @@
+// Host-side schedule planner of libddlsim: box dimensions -> per-step operation tables.
+// Pure integer code, no HIP; see include/ddlsim.h for the vocabulary.
+#pragma once
+
+#include <cstddef>
+#include <cstdint>
+#include <mutex>
+#include <vector>
+
+#include "../../include/ddlsim.h"
+
+namespace ddl {
+
+// One transfer of a phase: elements [off, off+n) of learner src go to learner dst.
+// Layout is shared with the kernels (read from device memory as-is).
+struct Op {
+    uint64_t off;
+    uint64_t n;
+    int32_t src;
+    int32_t dst;
+};
+static_assert(sizeof(Op) == 24, "Op is read by the kernels with this layout");
+
+struct Step {
+    int kind;        // DDL_STEP_REDUCE / DDL_STEP_GATHER
+    int dim;         // 0-based box dimension whose rings run in this phase
+    uint64_t max_n;  // longest operation of the phase (sizes the launch)
+    uint64_t bytes;  // memory traffic of the phase
+};
+
+struct DeviceTables {
+    int device = -1;
+    Op* ops = nullptr;       // num_steps * P operations, step-major
+    void** ptrs = nullptr;   // staging for the learner pointers when P exceeds the kernarg table
+};
+
+}  // namespace ddl
+
+struct ddl_plan {
+    std::vector<int> dims;
+    int P = 0;
+    uint64_t count = 0;
+    ddl_dtype_t dtype = DDL_F32;
+    int elem_size = 4;
+    int first_gather = 0;                 // index of the first all-gather step
+    std::vector<ddl::Step> steps;
+    std::vector<ddl::Op> ops;             // steps.size() * P, step-major, indexed by sender
+    std::vector<uint64_t> own_off, own_n; // finest chunk per learner
+    uint64_t bytes_total = 0;
+
+    mutable std::mutex mu;                      // guards `tables`
+    mutable std::vector<ddl::DeviceTables> tables;  // one entry per device the plan ran on
+};
+
+namespace ddl {
+
+int dtype_size(ddl_dtype_t dtype);  // 0 for an unknown type
+
+// Part k of d of [lo, hi), cut on granules of G elements.
+void split_range(uint64_t lo, uint64_t hi, uint64_t d, uint64_t k, uint64_t G,
+                 uint64_t* a, uint64_t* b);
+
+// Fills `plan` (dims, P, count, dtype already validated by the caller).
+void build_schedule(ddl_plan* plan);
+
+ddl_status_t validate_dims(const int* dims, int m, int P);
+
+}  // namespace ddl

@@ -1,0 +1,336 @@
+"""Parity of the HIP path against the CPU oracle, through the C ABI, on a real MI355X.
+
+Bar: bit-exact against the same-order oracle for every dtype; for fp32 additionally
+within 1e-5 (relative to sum_j |V_j|, and globally to max |R|) of the fp64 sum.
+torch is used for device memory, copies and equality checks only.
+"""
+import sys
+from math import prod
+
+import numpy as np
+import pytest
+import torch
+
+import oracle.ddl_oracle as O
+import paper_1708_02188_amd as D
+from paper_1708_02188_amd import inputs as I
+
+pytestmark = pytest.mark.gpu
+
+NP_OF = {D.DDL_F32: np.float32, D.DDL_F64: np.float64, D.DDL_I32: np.int32}
+TORCH_OF = {D.DDL_F32: torch.float32, D.DDL_F64: torch.float64, D.DDL_I32: torch.int32}
+
+
+def say(*a):
+    print(*a, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module")
+def dev():
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a device; run with -m 'not gpu' on a CPU box")
+    return torch.device("cuda:0")
+
+
+def upload(V, dev):
+    return [torch.from_numpy(np.ascontiguousarray(v)).to(dev) for v in V]
+
+
+def download(bufs):
+    torch.cuda.synchronize()
+    return [b.cpu().numpy() for b in bufs]
+
+
+def wide_inputs(rng, P, count, dtype):
+    if dtype == D.DDL_I32:
+        return [rng.integers(-2 ** 31, 2 ** 31, size=count, dtype=np.int64).astype(np.int32) for _ in range(P)]
+    npdt = NP_OF[dtype]
+    return [(rng.uniform(-1, 1, count) * 10.0 ** rng.uniform(-3, 3, count)).astype(npdt) for _ in range(P)]
+
+
+def assert_bitwise(got, want, what):
+    assert got.dtype == want.dtype and got.shape == want.shape, what
+    if got.tobytes() != want.tobytes():
+        bits = np.uint32 if got.dtype.itemsize == 4 else np.uint64
+        diff = np.flatnonzero(got.view(bits) != want.view(bits))
+        raise AssertionError(f"{what}: {len(diff)} elements differ, first at {diff[:5]} "
+                             f"got {got[diff[:5]]} want {want[diff[:5]]}")
+
+
+# ---------------------------------------------------------------------------------------
+# the generator: device fill == host fill
+# ---------------------------------------------------------------------------------------
+@pytest.mark.parametrize("dist", ["int8", "uniform", "normal"])
+def test_generator_device_equals_host(dev, dist):
+    for n, seed, learner, first in [(1, 1, 0, 0), (100003, I.BASE_SEED, 7, 12345), (1 << 20, 99, 255, 2 ** 33 + 1)]:
+        say(f"generator {dist} n={n} seed={seed} learner={learner} first={first}")
+        t = torch.empty(n, dtype=torch.float32, device=dev)
+        I.fill_device(t, seed, learner, dist, first)
+        torch.cuda.synchronize()
+        assert_bitwise(t.cpu().numpy(), I.fill_host(n, seed, learner, dist, first), dist)
+
+
+# ---------------------------------------------------------------------------------------
+# small and medium sizes: every learner, every element, against the step simulator
+# ---------------------------------------------------------------------------------------
+# one tile of the kernels is 4096 fp32 elements; counts span none, one, several tiles and ragged ends
+SMALL_CASES = [
+    ([1], 1000), ([2], 1), ([2], 4099), ([3], 100003), ([4], 16), ([4], 37), ([4], 65536 + 5),
+    ([5], 3), ([2, 3], 50001), ([4, 4], 8), ([4, 4], 300007), ([3, 1, 2], 70001), ([4, 2, 2], 262144 + 13),
+    ([2, 2, 2, 2], 99999), ([16], 150001), ([4, 16], 200003), ([4, 8, 8], 1000), ([4, 8, 8], 300001),
+    ([7, 3], 123457), ([2], 0),
+]
+
+
+@pytest.mark.parametrize("dims,count", SMALL_CASES)
+def test_allreduce_matches_step_simulator_fp32(dev, dims, count):
+    P = prod(dims)
+    say(f"allreduce f32 dims={dims} count={count}")
+    rng = np.random.default_rng(1000 + count + P)
+    V = wide_inputs(rng, P, count, D.DDL_F32)
+    bufs = upload(V, dev)
+    plan = D.ddl_ring_plan(dims, P, count)
+    D.ddl_allreduce_sim(bufs, P, plan, count, D.DDL_F32, torch.cuda.current_stream())
+    got = download(bufs)
+    want = O.allreduce_steps(V, dims)
+    for j in range(P):
+        assert_bitwise(got[j], want[j], f"dims={dims} count={count} learner={j}")
+    # value check: fp64 sum within the stated tolerance
+    if count:
+        ref = O.sum_fp64(V)
+        absum = sum(np.abs(v.astype(np.float64)) for v in V)
+        assert np.all(np.abs(got[0].astype(np.float64) - ref) <= 1e-5 * absum)
+
+
+@pytest.mark.parametrize("dims,count", [([4], 1 << 16), ([2, 3], 4097), ([4, 8, 8], 70000), ([3, 5], 12)])
+def test_integer_valued_inputs_give_the_exact_sum(dev, dims, count):
+    P = prod(dims)
+    say(f"allreduce integer-valued dims={dims} count={count}")
+    rng = np.random.default_rng(5)
+    V = [rng.integers(-8, 9, size=count).astype(np.float32) for _ in range(P)]
+    want = sum(v.astype(np.int64) for v in V)
+    bufs = upload(V, dev)
+    plan = D.ddl_ring_plan(dims, P, count)
+    D.ddl_allreduce_sim(bufs, P, plan, count)
+    for j, g in enumerate(download(bufs)):
+        assert np.array_equal(g.astype(np.int64), want), j
+
+
+@pytest.mark.parametrize("dtype", [D.DDL_F64, D.DDL_I32])
+@pytest.mark.parametrize("dims,count", [([4], 10001), ([2, 3], 65537), ([4, 4], 131072 + 3), ([3], 1)])
+def test_other_dtypes_match_step_simulator(dev, dtype, dims, count):
+    P = prod(dims)
+    say(f"allreduce dtype={dtype} dims={dims} count={count}")
+    rng = np.random.default_rng(77 + count)
+    V = wide_inputs(rng, P, count, dtype)
+    bufs = upload(V, dev)
+    plan = D.ddl_ring_plan(dims, P, count, dtype)
+    D.ddl_allreduce_sim(bufs, P, plan, count, dtype)
+    got = download(bufs)
+    with np.errstate(over="ignore"):
+        want = O.allreduce_steps(V, dims)
+    for j in range(P):
+        assert_bitwise(got[j], want[j], f"dtype={dtype} dims={dims} learner={j}")
+
+
+def test_hand_worked_example_on_device(dev):
+    from conftest import read_golden_ring_example
+    ex = read_golden_ring_example("ring4_cancellation.txt")
+    V = [np.full(16, v, dtype=np.float32) for v in ex["inputs"]]
+    bufs = upload(V, dev)
+    plan = D.ddl_ring_plan(ex["dims"], 4, 16)
+    D.ddl_allreduce_sim(bufs, 4, plan, 16)
+    for g in download(bufs):
+        assert np.array_equal(g, np.array(ex["expected"], dtype=np.float32))
+
+
+# ---------------------------------------------------------------------------------------
+# the two halves on their own, streams, repeated calls, views, many learners
+# ---------------------------------------------------------------------------------------
+@pytest.mark.parametrize("dims,count", [([4], 20003), ([2, 3], 9001), ([4, 2, 2], 100001)])
+def test_reduce_scatter_and_allgather_alone(dev, dims, count):
+    P = prod(dims)
+    say(f"reduce-scatter / all-gather dims={dims} count={count}")
+    rng = np.random.default_rng(31)
+    V = wide_inputs(rng, P, count, D.DDL_F32)
+    plan = D.ddl_ring_plan(dims, P, count)
+    bufs = upload(V, dev)
+    D.ddl_reduce_scatter_sim(bufs, P, plan, count)
+    got = download(bufs)
+    want = O.reduce_scatter_steps(V, dims)
+    for j in range(P):
+        assert_bitwise(got[j], want[j], f"reduce-scatter learner={j}")
+        off, n = D.ddl_plan_owned_chunk(plan, j)
+        assert_bitwise(got[j][off:off + n], O.allreduce_fold(V, dims)[off:off + n], f"owned chunk {j}")
+    D.ddl_allgather_sim(bufs, P, plan, count)
+    got = download(bufs)
+    want = O.allgather_steps(want, dims)
+    for j in range(P):
+        assert_bitwise(got[j], want[j], f"all-gather learner={j}")
+
+
+def test_side_stream_profile_entry_and_repeat(dev):
+    dims, count = [4, 4], 500009
+    P = 16
+    rng = np.random.default_rng(8)
+    V = wide_inputs(rng, P, count, D.DDL_F32)
+    want1 = O.allreduce_steps(V, dims)
+    want2 = O.allreduce_steps(want1, dims)
+    plan = D.ddl_ring_plan(dims, P, count)
+    D.ddl_plan_prepare(plan)
+    stream = torch.cuda.Stream()
+    bufs = upload(V, dev)
+    torch.cuda.synchronize()
+    say("side stream, two calls back to back")
+    with torch.cuda.stream(stream):
+        D.ddl_allreduce_sim(bufs, P, plan, count, D.DDL_F32, stream)
+        D.ddl_allreduce_sim(bufs, P, plan, count, D.DDL_F32, stream)
+    stream.synchronize()
+    for j, g in enumerate(download(bufs)):
+        assert_bitwise(g, want2[j], f"second call learner={j}")
+    say("profile entry")
+    bufs = upload(V, dev)
+    ms = D.ddl_allreduce_sim_profile(bufs, P, plan, count, D.DDL_F32, torch.cuda.current_stream())
+    assert len(ms) == 12 and all(x > 0 for x in ms)
+    for j, g in enumerate(download(bufs)):
+        assert_bitwise(g, want1[j], f"profile learner={j}")
+
+
+def test_buffers_as_aligned_views_of_one_allocation(dev):
+    dims, count, P = [2, 2], 10007, 4
+    stride = 10240  # elements; multiple of 4 -> 16-byte aligned views, non-overlapping
+    rng = np.random.default_rng(9)
+    V = wide_inputs(rng, P, count, D.DDL_F32)
+    slab = torch.zeros(P * stride, dtype=torch.float32, device=dev)
+    bufs = [slab[j * stride: j * stride + count] for j in range(P)]
+    for b, v in zip(bufs, V):
+        b.copy_(torch.from_numpy(v))
+    plan = D.ddl_ring_plan(dims, P, count)
+    D.ddl_allreduce_sim(bufs, P, plan, count)
+    want = O.allreduce_steps(V, dims)
+    for j, g in enumerate(download(bufs)):
+        assert_bitwise(g, want[j], f"view learner={j}")
+    # the gaps between the views stay untouched
+    torch.cuda.synchronize()
+    for j in range(P):
+        assert not slab[j * stride + count:(j + 1) * stride].any()
+    # misaligned and overlapping views are rejected before anything runs
+    with pytest.raises(D.DdlError) as e:
+        D.ddl_allreduce_sim([slab[1 + j * stride: 1 + j * stride + count] for j in range(P)], P, plan, count)
+    assert e.value.status == D.DDL_ERR_ALIGN
+    with pytest.raises(D.DdlError) as e:
+        D.ddl_allreduce_sim([slab[j * 5000: j * 5000 + count] for j in range(P)], P, plan, count)
+    assert e.value.status == D.DDL_ERR_ARG
+
+
+def test_more_learners_than_the_kernarg_table_holds(dev):
+    dims, count, P = [8, 8, 8], 70001, 512
+    say(f"P={P} dims={dims} count={count} (device pointer table path)")
+    V = [I.fill_host(count, 3, j, "uniform") for j in range(P)]
+    bufs = upload(V, dev)
+    plan = D.ddl_ring_plan(dims, P, count)
+    D.ddl_allreduce_sim(bufs, P, plan, count)
+    got = download(bufs)
+    want = O.allreduce_fold(V, dims)
+    for j in range(P):
+        assert_bitwise(got[j], want, f"learner={j}")
+
+
+# ---------------------------------------------------------------------------------------
+# the benchmark configurations at full size, device-generated inputs
+# ---------------------------------------------------------------------------------------
+def sample_ranges(plan, P, count, width=2048, extra=12):
+    """Element ranges the oracle recomputes: both ends of the buffer, both sides of a
+    selection of chunk boundaries (kernel tile tails sit there), and random places."""
+    rng = np.random.default_rng(count)
+    edges = {0, count}
+    for j in sorted(set([0, 1, P // 2, P - 1] + list(rng.integers(0, P, 4)))):
+        off, n = D.ddl_plan_owned_chunk(plan, int(j))
+        edges.update((off, off + n))
+    ranges = []
+    for e in sorted(edges):
+        ranges.append((max(0, e - width // 2), min(count, e + width // 2)))
+    for a in rng.integers(0, max(1, count - width), extra):
+        ranges.append((int(a), min(count, int(a) + width)))
+    return [(a, b) for a, b in ranges if b > a]
+
+
+def run_config(dev, cfg, full_compare):
+    P, dims, count, dist, seed = cfg["P"], cfg["dims"], cfg["count"], cfg["dist"], cfg["seed"]
+    say(f"config {cfg['name']}: P={P} dims={dims} count={count} dist={dist} seed={seed}")
+    bufs = [torch.empty(count, dtype=torch.float32, device=dev) for _ in range(P)]
+    for j, b in enumerate(bufs):
+        I.fill_device(b, seed, j, dist)
+    plan = D.ddl_ring_plan(dims, P, count)
+    torch.cuda.synchronize()
+    say("  inputs resident, launching")
+    D.ddl_allreduce_sim(bufs, P, plan, count, D.DDL_F32, torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    say("  allreduce done, checking learners agree")
+    for j in range(1, P):
+        assert torch.equal(bufs[0].view(torch.int32), bufs[j].view(torch.int32)), f"learner {j} differs from 0"
+    got = bufs[0].cpu().numpy()
+    del bufs
+    torch.cuda.empty_cache()
+
+    def get(r, a, b):
+        return I.fill_host(b - a, seed, r, dist, first=a)
+
+    ranges = [(0, count)] if full_compare else sample_ranges(plan, P, count)
+    say(f"  oracle on {len(ranges)} ranges, {sum(b - a for a, b in ranges)} elements")
+    worst_rel = 0.0
+    for a, b in ranges:
+        want = O.allreduce_fold_range(get, dims, count, a, b, np.float32)
+        assert_bitwise(got[a:b], want, f"{cfg['name']} elements [{a},{b})")
+        if not full_compare or b - a <= 1 << 22:
+            V = [get(r, a, b) for r in range(P)]
+            ref = O.sum_fp64(V)
+            absum = sum(np.abs(v.astype(np.float64)) for v in V)
+            err = np.abs(got[a:b].astype(np.float64) - ref)
+            assert np.all(err <= 1e-5 * absum)
+            if dist == "int8":
+                assert np.array_equal(got[a:b].astype(np.float64), ref)  # integers: exact
+            worst_rel = max(worst_rel, float(np.max(err)) / max(float(np.max(np.abs(ref))), 1e-30))
+    assert worst_rel <= 1e-5
+    say(f"  ok, worst |x - fp64| / max|fp64| = {worst_rel:.2e}")
+
+
+def test_config1_ring4_integer_exact(dev):
+    run_config(dev, I.CONFIGS[0], full_compare=True)
+
+
+def test_config2_box4x4_resnet50_full_compare(dev):
+    cfg = I.CONFIGS[1]
+    run_config(dev, cfg, full_compare=True)
+
+
+def test_config2_first_range_fp64(dev):
+    # fp64 closeness over a 4 M element prefix of the ResNet-50-sized buffer
+    cfg = dict(I.CONFIGS[1])
+    P, dims, count = cfg["P"], cfg["dims"], cfg["count"]
+    bufs = [torch.empty(count, dtype=torch.float32, device=dev) for _ in range(P)]
+    for j, b in enumerate(bufs):
+        I.fill_device(b, cfg["seed"], j, cfg["dist"])
+    plan = D.ddl_ring_plan(dims, P, count)
+    D.ddl_allreduce_sim(bufs, P, plan, count)
+    torch.cuda.synchronize()
+    n = 1 << 22
+    got = bufs[3][:n].cpu().numpy().astype(np.float64)
+    V = [I.fill_host(n, cfg["seed"], r, cfg["dist"]) for r in range(P)]
+    ref = O.sum_fp64(V)
+    absum = sum(np.abs(v.astype(np.float64)) for v in V)
+    assert np.all(np.abs(got - ref) <= 1e-5 * absum)
+    assert np.max(np.abs(got - ref)) <= 1e-5 * np.max(np.abs(ref))
+
+
+def test_config3_box4x16_resnet50_layers(dev):
+    run_config(dev, I.CONFIGS[2], full_compare=False)
+
+
+def test_config4_box4x8x8_resnet50(dev):
+    run_config(dev, I.CONFIGS[3], full_compare=False)
+
+
+def test_config5_box4x8x8_resnet101_22k(dev):
+    run_config(dev, I.CONFIGS[4], full_compare=False)

@@ -533,6 +533,16 @@ def test_mutation_fold_wrong_start(monkeypatch):
             out[a:b] = A[()]
         return out
 
-    monkeypatch.setattr(O, "allreduce_fold", fold_from_owner)
+    monkeypatch.setattr(O, "allreduce_fold", fold_from_owner)  # replaces the whole-buffer entry
     with pytest.raises(AssertionError):
         pin_steps_equal_fold(dims_list=[[4], [3, 2]], counts=(257,))
+
+
+def test_fold_range_equals_whole_fold():
+    rng = np.random.default_rng(13)
+    dims, count = [3, 2, 2], 1003
+    V = wide_fp32_inputs(rng, 12, count)
+    whole = O.allreduce_fold(V, dims)
+    for lo, hi in [(0, 0), (0, 1), (5, 900), (998, 1003), (83, 84), (0, 1003)]:
+        part = O.allreduce_fold_range(lambda r, a, b: V[r][a:b], dims, count, lo, hi, np.float32)
+        assert part.tobytes() == whole[lo:hi].tobytes()
