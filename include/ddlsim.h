@@ -88,12 +88,16 @@ ddl_status_t ddl_plan_prepare(const ddl_plan_t* plan);
  *   bufs   HOST array of P DEVICE pointers; bufs[j] is learner j's buffer of at least
  *          `count` elements, 16-byte aligned, pairwise distinct and non-overlapping,
  *          owned by the caller.  The array itself may be reused as soon as the call returns.
+ *          With count == 0 the pointers are not examined (empty buffers may be NULL).
  *   P, count, dtype must equal the plan's.
- * Enqueues one kernel per step on `stream` and returns without synchronising; when the
- * stream has drained, every bufs[j] holds the sum, bit-identical across learners, formed
- * in the order the schedule fixes: within the ring of dimension t the partial sum of part
- * k starts at ring position k+1 and is extended by positions k+2, ..., k+d_t (= k).
- * A plan may be used from several streams at once only with disjoint buffers and P <= 256.
+ * Enqueues one small kernel that binds the plan's operations to these buffers, then one
+ * kernel per step, all on `stream`, and returns without synchronising; when the stream has
+ * drained, every bufs[j] holds the sum, bit-identical across learners, formed in the order
+ * the schedule fixes: within the ring of dimension t the partial sum of part k starts at
+ * ring position k+1 and is extended by positions k+2, ..., k+d_t (= k).
+ * The binding lives in the plan's device tables: calls that share a plan must be ordered
+ * with respect to each other (same stream, or synchronised by the caller); use one plan
+ * per stream for concurrent allreduces.
  * Errors are reported before anything is enqueued, except DDL_ERR_HIP for a failed launch.
  */
 ddl_status_t ddl_allreduce_sim(void** bufs, int P, const ddl_plan_t* plan, size_t count,

@@ -39,10 +39,16 @@ ddl_status_t device_tables(const ddl_plan* plan, DeviceTables* out) {
             (void)hipFree(t.ops);
             return DDL_ERR_HIP;
         }
+        if (hipMalloc(reinterpret_cast<void**>(&t.rops),
+                      plan->ops.size() * sizeof(ddl::ResolvedOp)) != hipSuccess) {
+            (void)hipFree(t.ops);
+            return DDL_ERR_NOMEM;
+        }
     }
     if (plan->P > ddl::kKernargLearners) {
         if (hipMalloc(reinterpret_cast<void**>(&t.ptrs), size_t(plan->P) * sizeof(void*)) != hipSuccess) {
             if (t.ops) (void)hipFree(t.ops);
+            if (t.rops) (void)hipFree(t.rops);
             return DDL_ERR_NOMEM;
         }
     }
@@ -55,6 +61,7 @@ ddl_status_t check_call(void** bufs, int P, const ddl_plan* plan, size_t count, 
     if (plan == nullptr || bufs == nullptr || P < 1) return DDL_ERR_ARG;
     if (ddl::dtype_size(dtype) == 0) return DDL_ERR_DTYPE;
     if (P != plan->P || count != plan->count || dtype != plan->dtype) return DDL_ERR_PLAN_MISMATCH;
+    if (count == 0) return DDL_OK;  // nothing will be touched: empty buffers may be NULL
     for (int j = 0; j < P; ++j) {
         if (bufs[j] == nullptr) return DDL_ERR_ARG;
         if (reinterpret_cast<uintptr_t>(bufs[j]) % 16 != 0) return DDL_ERR_ALIGN;
@@ -96,10 +103,12 @@ ddl_status_t run_steps(void** bufs, int P, const ddl_plan* plan, size_t count, d
             return DDL_ERR_HIP;
         d_ptrs = tables.ptrs;
     }
+    // bind the plan's operations to these buffers (stream-ordered before the steps)
+    if (ddl::launch_resolve(*plan, tables.ops, tables.rops, table, d_ptrs, stream) != hipSuccess)
+        return DDL_ERR_HIP;
     if (events && hipEventRecord(events[0], stream) != hipSuccess) return DDL_ERR_HIP;
     for (int s = first; s < last; ++s) {
-        if (ddl::launch_step(*plan, plan->steps[s], tables.ops + size_t(s) * P, table, d_ptrs,
-                             stream) != hipSuccess)
+        if (ddl::launch_step(*plan, plan->steps[s], tables.rops + size_t(s) * P, stream) != hipSuccess)
             return DDL_ERR_HIP;
         if (events && hipEventRecord(events[s - first + 1], stream) != hipSuccess) return DDL_ERR_HIP;
     }
@@ -145,6 +154,7 @@ void ddl_plan_free(ddl_plan_t* plan) {
     if (plan == nullptr) return;
     for (const DeviceTables& t : plan->tables) {
         if (t.ops) (void)hipFree(t.ops);
+        if (t.rops) (void)hipFree(t.rops);
         if (t.ptrs) (void)hipFree(t.ptrs);
     }
     delete plan;

@@ -8,16 +8,21 @@
 namespace ddl {
 
 // Learner base pointers travel in the kernel-argument segment when they fit, so a call
-// needs no host-to-device copy and a plan can serve several streams at once.
+// needs no host-to-device copy of its own.
 constexpr int kKernargLearners = 256;
 struct PtrTable {
     void* p[kKernargLearners];
 };
 
-// Enqueue the kernel of one step.  d_ops points at that step's P operations in device
-// memory.  Learner pointers come from `table` (P <= kKernargLearners) or, if d_ptrs is not
-// NULL, from that device array.  A step that moves nothing enqueues nothing.
-hipError_t launch_step(const ddl_plan& plan, const Step& step, const Op* d_ops,
-                       const PtrTable& table, void* const* d_ptrs, hipStream_t stream);
+// Enqueue the kernel that fills d_rops (one ResolvedOp per entry of the plan's operation
+// table d_ops) for the learner pointers in `table` (P <= kKernargLearners) or, if d_ptrs is
+// not NULL, in that device array.
+hipError_t launch_resolve(const ddl_plan& plan, const Op* d_ops, ResolvedOp* d_rops,
+                          const PtrTable& table, void* const* d_ptrs, hipStream_t stream);
+
+// Enqueue the kernel of one step.  d_rops points at that step's P resolved operations in
+// device memory.  A step that moves nothing enqueues nothing.
+hipError_t launch_step(const ddl_plan& plan, const Step& step, const ResolvedOp* d_rops,
+                       hipStream_t stream);
 
 }  // namespace ddl

@@ -4,33 +4,44 @@
 //   reduce_add_step : dst[off .. off+n) <- dst[..] + src[..]   (Sec. 4.1 ReduceScatter phase)
 //   copy_step       : dst[off .. off+n) <- src[..]             (Sec. 4.1 AllGather phase,
 //                                                               i.e. the paper's assignment)
+//   resolve_ops     : per call, turns the plan's (learner, offset) operations into absolute
+//                     (src address, dst address, length) records for the caller's buffers
 //
-// Both stream through HBM once: 12 resp. 8 bytes of traffic per fp32 element and one add,
-// so the bound is memory bandwidth.  No LDS (every element is touched by exactly one
-// lane), no MFMA (nothing is contracted).  Each lane moves 16-byte vectors
-// (global_load/store_dwordx4); a wave covers 1 KiB per instruction, and every lane keeps
-// DDL_UNROLL such loads per operand in flight before the first use.  The sum is formed in
-// the element type with one rounding per add; the build disables packed-fp32 instructions.
+// The two phase kernels stream through HBM once: 12 resp. 8 bytes of traffic per fp32
+// element and one add, so the bound is memory bandwidth.  No LDS (every element is touched
+// by exactly one lane), no MFMA (nothing is contracted).  Each lane moves 16-byte vectors
+// (global_load/store_dwordx4, non-temporal), so one wave instruction covers 1 KiB.
+//
+// Shape, from measurement on MI355X: the highest sustained bandwidth comes from very many
+// small workgroups (one wave, one 1 KiB vector row per operand) dispatched in address
+// order, not from persistent or deeply unrolled loops: the set of rows in flight then
+// stays a narrow window that slides through memory.  A workgroup that small lives only a
+// few memory latencies, so its prologue must be short: the operation record is one
+// 32-byte scalar load from a table of absolute addresses (written by resolve_ops), and
+// the table pointer is a preloaded kernel argument.
 //
 // Grid: blockIdx.y = operation (sending learner), blockIdx.x strides over that
 // operation's tiles.  Consecutive workgroups are handed to the 8 XCDs round-robin, so
 // neighbouring tiles of one chunk stream through different L2s/channels in parallel; there
 // is no reuse to keep local to one XCD.
+//
+// The sum is formed in the element type with one rounding per add; the build disables
+// packed-fp32 instructions and floating-point contraction.
 #include <hip/hip_runtime.h>
 
 #include "kernels.h"
 
 #ifndef DDL_THREADS
-#define DDL_THREADS 256
+#define DDL_THREADS 64
 #endif
 #ifndef DDL_UNROLL
-#define DDL_UNROLL 4
+#define DDL_UNROLL 1
 #endif
 #ifndef DDL_NT_LOAD
 #define DDL_NT_LOAD 1
 #endif
 #ifndef DDL_NT_STORE
-#define DDL_NT_STORE 0
+#define DDL_NT_STORE 1
 #endif
 
 namespace ddl {
@@ -61,31 +72,53 @@ template <typename V> __device__ __forceinline__ void stream_store(DDL_GLOBAL V*
 #endif
 }
 
+// One thread per (step, sender): absolute addresses for this call's buffers.
+__global__ __launch_bounds__(256) void resolve_ops(const PtrTable table, void* const* __restrict__ d_ptrs,
+                                                   const Op* __restrict__ ops, ResolvedOp* __restrict__ out,
+                                                   unsigned total, unsigned elem_size) {
+    const unsigned i = blockIdx.x * 256u + threadIdx.x;
+    if (i >= total) return;
+    const Op op = ops[i];
+    const uint64_t byte_off = op.off * elem_size;
+    const uint64_t src = reinterpret_cast<uint64_t>(d_ptrs ? d_ptrs[op.src] : table.p[op.src]);
+    const uint64_t dst = reinterpret_cast<uint64_t>(d_ptrs ? d_ptrs[op.dst] : table.p[op.dst]);
+    ResolvedOp r;
+    r.src = src + byte_off;
+    r.dst = dst + byte_off;
+    r.n = op.n;
+    r.reserved = 0;
+    out[i] = r;
+}
+
+typedef uint64_t u64x4 __attribute__((ext_vector_type(4)));
+
+// Rows of one wave (64 lanes x 16 bytes) are laid on absolute 1 KiB boundaries of the
+// destination, whatever the chunk offset: a row that straddles cache lines would be fetched
+// and partially written by two different XCDs.
+constexpr uint64_t kRowBytes = 1024;
+constexpr uint64_t kRowVecs = kRowBytes / 16;
+
 template <typename T, bool REDUCE>
-__global__ __launch_bounds__(DDL_THREADS) void step_kernel(const PtrTable table,
-                                                           void* const* __restrict__ d_ptrs,
-                                                           const Op* __restrict__ ops) {
+__global__ __launch_bounds__(DDL_THREADS) void step_kernel(const ResolvedOp* __restrict__ rops,
+                                                           unsigned tile_stride) {
     typedef typename Vec16<T>::type V;
-    constexpr uint64_t VL = 16 / sizeof(T);                             // elements per vector
-    constexpr uint64_t TILE = uint64_t(DDL_THREADS) * DDL_UNROLL * VL;  // elements per tile
+    constexpr int64_t VL = 16 / sizeof(T);                          // elements per vector
+    constexpr int64_t TILE = int64_t(DDL_THREADS) * DDL_UNROLL;     // vectors per tile
 
-    const Op* op = ops + blockIdx.y;
-    const uint64_t n = op->n;
-    const uint64_t off = op->off;
-    const int si = __builtin_amdgcn_readfirstlane(op->src);
-    const int di = __builtin_amdgcn_readfirstlane(op->dst);
-    const DDL_GLOBAL T* src_base =
-        (const DDL_GLOBAL T*)(static_cast<const T*>(d_ptrs ? d_ptrs[si] : table.p[si])) + off;
-    DDL_GLOBAL T* dst_base = (DDL_GLOBAL T*)(static_cast<T*>(d_ptrs ? d_ptrs[di] : table.p[di])) + off;
-    const unsigned tid = threadIdx.x;
+    // the whole record in one scalar load: {src address, dst address, n, -}
+    const u64x4 rec = *reinterpret_cast<const u64x4*>(rops + blockIdx.y);
+    const DDL_GLOBAL V* src = (const DDL_GLOBAL V*)rec.x;
+    DDL_GLOBAL V* dst = (DDL_GLOBAL V*)rec.y;
+    const int64_t n = int64_t(rec.z);
+    const int64_t nv = n / VL;                                      // whole vectors
+    const int64_t shift = int64_t((rec.y % kRowBytes) / 16);        // vectors past a row boundary
+    const int64_t tid = threadIdx.x;
 
-    for (uint64_t base = uint64_t(blockIdx.x) * TILE; base < n; base += uint64_t(gridDim.x) * TILE) {
-        const DDL_GLOBAL T* src = src_base + base;
-        DDL_GLOBAL T* dst = dst_base + base;
-        const uint64_t rem = n - base;
-        if (rem >= TILE) {
-            const DDL_GLOBAL V* s = (const DDL_GLOBAL V*)src + tid;
-            DDL_GLOBAL V* d = (DDL_GLOBAL V*)dst + tid;
+    // vector index v of the operation <-> slot v + shift of the row-aligned tiling
+    for (int64_t first = int64_t(blockIdx.x) * TILE - shift; first <= nv; first += int64_t(tile_stride) * TILE) {
+        if (first >= 0 && first + TILE <= nv) {
+            const DDL_GLOBAL V* s = src + first + tid;
+            DDL_GLOBAL V* d = dst + first + tid;
             V a[DDL_UNROLL];
             V b[DDL_UNROLL];
 #pragma unroll
@@ -99,51 +132,66 @@ __global__ __launch_bounds__(DDL_THREADS) void step_kernel(const PtrTable table,
 #pragma unroll
             for (int u = 0; u < DDL_UNROLL; ++u) stream_store(d + u * DDL_THREADS, a[u]);
         } else {
-            // ragged end of an operation: whole vectors first, then single elements
-            const uint64_t nvec = rem / VL;
-            const DDL_GLOBAL V* s = (const DDL_GLOBAL V*)src;
-            DDL_GLOBAL V* d = (DDL_GLOBAL V*)dst;
-            for (uint64_t i = tid; i < nvec; i += DDL_THREADS) {
-                V a = s[i];
-                if (REDUCE) a = d[i] + a;
-                d[i] = a;
-            }
-            for (uint64_t i = nvec * VL + tid; i < rem; i += DDL_THREADS) {
-                T a = src[i];
-                if (REDUCE) a = dst[i] + a;
-                dst[i] = a;
+            // first or last tile of the operation: per-lane bounds
+#pragma unroll
+            for (int u = 0; u < DDL_UNROLL; ++u) {
+                const int64_t v = first + u * DDL_THREADS + tid;
+                if (v >= 0 && v < nv) {
+                    V a = src[v];
+                    if (REDUCE) a = dst[v] + a;
+                    dst[v] = a;
+                } else if (v == nv) {
+                    // the buffer's last, short vector: element by element
+                    const DDL_GLOBAL T* se = (const DDL_GLOBAL T*)(src + nv);
+                    DDL_GLOBAL T* de = (DDL_GLOBAL T*)(dst + nv);
+                    for (int64_t e = 0; e < n - nv * VL; ++e) {
+                        T a = se[e];
+                        if (REDUCE) a = de[e] + a;
+                        de[e] = a;
+                    }
+                }
             }
         }
     }
 }
 
 template <typename T>
-hipError_t launch_typed(const ddl_plan& plan, const Step& step, const Op* d_ops,
-                        const PtrTable& table, void* const* d_ptrs, hipStream_t stream) {
-    constexpr uint64_t TILE = uint64_t(DDL_THREADS) * DDL_UNROLL * (16 / sizeof(T));
-    uint64_t tiles = (step.max_n + TILE - 1) / TILE;
+hipError_t launch_typed(const ddl_plan& plan, const Step& step, const ResolvedOp* d_rops,
+                        hipStream_t stream) {
+    constexpr uint64_t VL = 16 / sizeof(T);
+    constexpr uint64_t TILE = uint64_t(DDL_THREADS) * DDL_UNROLL;  // vectors
+    // slots to cover: the whole vectors, one for a short last vector, and the row shift
+    uint64_t tiles = (step.max_n / VL + 1 + (kRowVecs - 1) + TILE - 1) / TILE;
     // keep gridDim.x * gridDim.y * blockDim.x below 2^32; the kernel strides over the rest
     const uint64_t max_x = ((uint64_t(1) << 32) / DDL_THREADS - 1) / uint64_t(plan.P);
     if (tiles > max_x) tiles = max_x;
-    if (tiles == 0) return hipSuccess;
     const dim3 grid(static_cast<unsigned>(tiles), static_cast<unsigned>(plan.P), 1);
     const dim3 block(DDL_THREADS, 1, 1);
     if (step.kind == DDL_STEP_REDUCE)
-        hipLaunchKernelGGL((step_kernel<T, true>), grid, block, 0, stream, table, d_ptrs, d_ops);
+        hipLaunchKernelGGL((step_kernel<T, true>), grid, block, 0, stream, d_rops, grid.x);
     else
-        hipLaunchKernelGGL((step_kernel<T, false>), grid, block, 0, stream, table, d_ptrs, d_ops);
+        hipLaunchKernelGGL((step_kernel<T, false>), grid, block, 0, stream, d_rops, grid.x);
     return hipGetLastError();
 }
 
 }  // namespace
 
-hipError_t launch_step(const ddl_plan& plan, const Step& step, const Op* d_ops,
-                       const PtrTable& table, void* const* d_ptrs, hipStream_t stream) {
+hipError_t launch_resolve(const ddl_plan& plan, const Op* d_ops, ResolvedOp* d_rops,
+                          const PtrTable& table, void* const* d_ptrs, hipStream_t stream) {
+    const unsigned total = static_cast<unsigned>(plan.ops.size());
+    if (total == 0) return hipSuccess;
+    hipLaunchKernelGGL(resolve_ops, dim3((total + 255) / 256), dim3(256), 0, stream, table, d_ptrs,
+                       d_ops, d_rops, total, static_cast<unsigned>(plan.elem_size));
+    return hipGetLastError();
+}
+
+hipError_t launch_step(const ddl_plan& plan, const Step& step, const ResolvedOp* d_rops,
+                       hipStream_t stream) {
     if (step.max_n == 0) return hipSuccess;
     switch (plan.dtype) {
-        case DDL_F32: return launch_typed<float>(plan, step, d_ops, table, d_ptrs, stream);
-        case DDL_F64: return launch_typed<double>(plan, step, d_ops, table, d_ptrs, stream);
-        case DDL_I32: return launch_typed<unsigned>(plan, step, d_ops, table, d_ptrs, stream);
+        case DDL_F32: return launch_typed<float>(plan, step, d_rops, stream);
+        case DDL_F64: return launch_typed<double>(plan, step, d_rops, stream);
+        case DDL_I32: return launch_typed<unsigned>(plan, step, d_rops, stream);
     }
     return hipErrorInvalidValue;
 }

@@ -21,6 +21,15 @@ struct Op {
 };
 static_assert(sizeof(Op) == 24, "Op is read by the kernels with this layout");
 
+// An operation bound to one call's buffers: absolute device addresses, length in elements.
+struct ResolvedOp {
+    uint64_t src;
+    uint64_t dst;
+    uint64_t n;
+    uint64_t reserved;
+};
+static_assert(sizeof(ResolvedOp) == 32, "one 32-byte scalar load per workgroup");
+
 struct Step {
     int kind;        // DDL_STEP_REDUCE / DDL_STEP_GATHER
     int dim;         // 0-based box dimension whose rings run in this phase
@@ -30,8 +39,9 @@ struct Step {
 
 struct DeviceTables {
     int device = -1;
-    Op* ops = nullptr;       // num_steps * P operations, step-major
-    void** ptrs = nullptr;   // staging for the learner pointers when P exceeds the kernarg table
+    Op* ops = nullptr;           // num_steps * P operations, step-major
+    ResolvedOp* rops = nullptr;  // the same operations bound to the buffers of the latest call
+    void** ptrs = nullptr;       // staging for the learner pointers when P exceeds the kernarg table
 };
 
 }  // namespace ddl
