@@ -29,8 +29,11 @@ def main():
     ap.add_argument("--config", type=int, default=2, help="1-based index into the five configurations")
     ap.add_argument("--sets-gib", type=float, default=96.0,
                     help="HBM budget for distinct input sets (one per step until it is used up)")
-    ap.add_argument("--profile-passes", type=int, default=5)
+    ap.add_argument("--profile-passes", type=int, default=10)
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
+    ap.add_argument("--calib-copy-mib", type=int, default=0,
+                    help="also run one plain device-to-device copy of this many MiB (a dispatch of "
+                         "known size, to scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
 
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -90,23 +93,30 @@ def main():
     same = all(torch.equal(last[0].view(torch.int32), last[j].view(torch.int32)) for j in range(1, P))
 
     # Roofline of the dominant kernel (the reduce-add phase kernel carries 12 of every 20
-    # bytes): HIP events round every phase, on the stream the kernels run on.
+    # bytes): HIP events on the stream the kernels run on, one pair round each half of the
+    # allreduce, so that the average launch duration includes kernel-to-kernel gaps but no
+    # event overhead between launches.
     kinds = [D.ddl_plan_get_step(plan, s)[0] for s in range(nsteps)]
     step_bytes = [D.ddl_plan_step_bytes(plan, s) for s in range(nsteps)]
     acc_ms = {D.DDL_STEP_REDUCE: 0.0, D.DDL_STEP_GATHER: 0.0}
     acc_bytes = {D.DDL_STEP_REDUCE: 0, D.DDL_STEP_GATHER: 0}
     launches = {D.DDL_STEP_REDUCE: 0, D.DDL_STEP_GATHER: 0}
-    per_step_ms = [0.0] * nsteps
     for p in range(args.profile_passes):
         for j, b in enumerate(sets[p % n_sets]):
             I.fill_device(b, seed + 7777 + p, j, dist, 0, stream)
-        ms = D.ddl_allreduce_sim_profile(sets[p % n_sets], P, plan, count, D.DDL_F32, stream)
+        r_ms, g_ms = D.ddl_allreduce_sim_timed(sets[p % n_sets], P, plan, count, D.DDL_F32, stream)
+        acc_ms[D.DDL_STEP_REDUCE] += r_ms
+        acc_ms[D.DDL_STEP_GATHER] += g_ms
         for s in range(nsteps):
             if step_bytes[s]:
-                acc_ms[kinds[s]] += ms[s]
                 acc_bytes[kinds[s]] += step_bytes[s]
                 launches[kinds[s]] += 1
-                per_step_ms[s] += ms[s] / args.profile_passes
+    # per-phase times (diagnostic only: an event pair round every launch adds a few us each)
+    per_step_ms = [0.0] * nsteps
+    if args.profile_passes:
+        for j, b in enumerate(sets[0]):
+            I.fill_device(b, seed + 9999, j, dist, 0, stream)
+        per_step_ms = D.ddl_allreduce_sim_profile(sets[0], P, plan, count, D.DDL_F32, stream)
 
     def kernel_line(kind, name):
         if not launches[kind]:
@@ -139,6 +149,14 @@ def main():
 
     del sets
     torch.cuda.empty_cache()
+
+    if args.calib_copy_mib > 0:
+        a = torch.zeros(args.calib_copy_mib * 2 ** 18, dtype=torch.float32, device=dev)
+        b = torch.empty_like(a)
+        torch.cuda.synchronize()
+        b.copy_(a)
+        torch.cuda.synchronize()
+        del a, b
 
     cpu = None
     if not args.no_cpu:

@@ -125,6 +125,17 @@ ddl_status_t ddl_allgather_sim(void** bufs, int P, const ddl_plan_t* plan, size_
 ddl_status_t ddl_allreduce_sim_profile(void** bufs, int P, const ddl_plan_t* plan, size_t count,
                                        ddl_dtype_t dtype, void* stream, float* step_ms);
 
+/*
+ * ddl_allreduce_sim with only three HIP events on `stream`: before the first reduce-scatter
+ * step, between the halves, after the last all-gather step.  SYNCHRONISES the stream.
+ * *reduce_ms / *gather_ms (host, either may be NULL) receive the elapsed milliseconds of
+ * each half, kernel-to-kernel gaps included; dividing by the number of steps of that kind
+ * gives the average launch duration of the reduce-add resp. copy kernel.
+ */
+ddl_status_t ddl_allreduce_sim_timed(void** bufs, int P, const ddl_plan_t* plan, size_t count,
+                                     ddl_dtype_t dtype, void* stream, float* reduce_ms,
+                                     float* gather_ms);
+
 /* ---- plan introspection (host only) ------------------------------------------------ */
 
 /* 2 * sum_t (d_t - 1): Sec. 4.3, d-1 phases per ring, once reducing and once gathering.

@@ -34,6 +34,8 @@ def _load():
         "ddl_reduce_scatter_sim": (i, sim_args),
         "ddl_allgather_sim": (i, sim_args),
         "ddl_allreduce_sim_profile": (i, sim_args + [ctypes.POINTER(ctypes.c_float)]),
+        "ddl_allreduce_sim_timed": (i, sim_args + [ctypes.POINTER(ctypes.c_float),
+                                                   ctypes.POINTER(ctypes.c_float)]),
         "ddl_plan_num_steps": (i, [vp]),
         "ddl_plan_num_learners": (i, [vp]),
         "ddl_plan_bytes_moved": (sz, [vp]),
@@ -141,6 +143,14 @@ def ddl_allreduce_sim_profile(bufs, P, plan, count, dtype=DDL_F32, stream=None):
     _check(_lib.ddl_allreduce_sim_profile(_ptr_array(bufs), P, _h(plan), count, dtype,
                                           _stream(stream), ms), "ddl_allreduce_sim_profile")
     return list(ms)[:n]
+
+
+def ddl_allreduce_sim_timed(bufs, P, plan, count, dtype=DDL_F32, stream=None):
+    """Returns (reduce_ms, gather_ms): elapsed time of the two halves."""
+    r, g = ctypes.c_float(0), ctypes.c_float(0)
+    _check(_lib.ddl_allreduce_sim_timed(_ptr_array(bufs), P, _h(plan), count, dtype, _stream(stream),
+                                        ctypes.byref(r), ctypes.byref(g)), "ddl_allreduce_sim_timed")
+    return r.value, g.value
 
 
 def ddl_plan_num_steps(plan):

@@ -79,33 +79,37 @@ ddl_status_t check_call(void** bufs, int P, const ddl_plan* plan, size_t count, 
 }
 
 // Run steps [first, last) of the plan.  events: NULL, or last-first+1 created events that
-// are recorded round every launch.
+// are recorded round every launch.  bind: first write the resolved operation table for
+// `bufs` (false only when an earlier call on the same stream has just bound them).
 ddl_status_t run_steps(void** bufs, int P, const ddl_plan* plan, size_t count, ddl_dtype_t dtype,
-                       void* stream_v, int first, int last, hipEvent_t* events) {
+                       void* stream_v, int first, int last, hipEvent_t* events, bool bind = true) {
     ddl_status_t st = check_call(bufs, P, plan, count, dtype);
     if (st != DDL_OK) return st;
     hipStream_t stream = static_cast<hipStream_t>(stream_v);
-    if (first >= last || count == 0) return DDL_OK;
+    if (count == 0 || plan->steps.empty()) return DDL_OK;
+    if (first >= last && !bind) return DDL_OK;
 
     DeviceTables tables;
     st = device_tables(plan, &tables);
     if (st != DDL_OK) return st;
 
-    PtrTable table;
-    void* const* d_ptrs = nullptr;
-    if (P <= ddl::kKernargLearners) {
-        std::memset(&table, 0, sizeof(table));
-        std::memcpy(table.p, bufs, size_t(P) * sizeof(void*));
-    } else {
-        // pageable source: the runtime has copied the array out before this returns
-        if (hipMemcpyAsync(tables.ptrs, bufs, size_t(P) * sizeof(void*), hipMemcpyHostToDevice,
-                           stream) != hipSuccess)
+    if (bind) {
+        PtrTable table;
+        void* const* d_ptrs = nullptr;
+        if (P <= ddl::kKernargLearners) {
+            std::memset(&table, 0, sizeof(table));
+            std::memcpy(table.p, bufs, size_t(P) * sizeof(void*));
+        } else {
+            // pageable source: the runtime has copied the array out before this returns
+            if (hipMemcpyAsync(tables.ptrs, bufs, size_t(P) * sizeof(void*), hipMemcpyHostToDevice,
+                               stream) != hipSuccess)
+                return DDL_ERR_HIP;
+            d_ptrs = tables.ptrs;
+        }
+        // bind the plan's operations to these buffers (stream-ordered before the steps)
+        if (ddl::launch_resolve(*plan, tables.ops, tables.rops, table, d_ptrs, stream) != hipSuccess)
             return DDL_ERR_HIP;
-        d_ptrs = tables.ptrs;
     }
-    // bind the plan's operations to these buffers (stream-ordered before the steps)
-    if (ddl::launch_resolve(*plan, tables.ops, tables.rops, table, d_ptrs, stream) != hipSuccess)
-        return DDL_ERR_HIP;
     if (events && hipEventRecord(events[0], stream) != hipSuccess) return DDL_ERR_HIP;
     for (int s = first; s < last; ++s) {
         if (ddl::launch_step(*plan, plan->steps[s], tables.rops + size_t(s) * P, stream) != hipSuccess)
@@ -206,6 +210,41 @@ ddl_status_t ddl_allreduce_sim_profile(void** bufs, int P, const ddl_plan_t* pla
                 hipEventElapsedTime(&step_ms[s], events[s], events[s + 1]) != hipSuccess)
                 st = DDL_ERR_HIP;
     for (hipEvent_t e : events)
+        if (e) (void)hipEventDestroy(e);
+    return st;
+}
+
+ddl_status_t ddl_allreduce_sim_timed(void** bufs, int P, const ddl_plan_t* plan, size_t count,
+                                     ddl_dtype_t dtype, void* stream, float* reduce_ms,
+                                     float* gather_ms) {
+    ddl_status_t st = check_call(bufs, P, plan, count, dtype);
+    if (st != DDL_OK) return st;
+    if (reduce_ms) *reduce_ms = 0.0f;
+    if (gather_ms) *gather_ms = 0.0f;
+    const int steps = static_cast<int>(plan->steps.size());
+    if (steps == 0 || count == 0) return DDL_OK;
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+    hipEvent_t ev[3] = {nullptr, nullptr, nullptr};
+    for (int i = 0; i < 3 && st == DDL_OK; ++i)
+        if (hipEventCreate(&ev[i]) != hipSuccess) st = DDL_ERR_HIP;
+    // bind first (untimed), then the two halves between events
+    if (st == DDL_OK) st = run_steps(bufs, P, plan, count, dtype, stream, 0, 0, nullptr, true);
+    if (st == DDL_OK && hipEventRecord(ev[0], hs) != hipSuccess) st = DDL_ERR_HIP;
+    if (st == DDL_OK)
+        st = run_steps(bufs, P, plan, count, dtype, stream, 0, plan->first_gather, nullptr, false);
+    if (st == DDL_OK && hipEventRecord(ev[1], hs) != hipSuccess) st = DDL_ERR_HIP;
+    if (st == DDL_OK)
+        st = run_steps(bufs, P, plan, count, dtype, stream, plan->first_gather, steps, nullptr, false);
+    if (st == DDL_OK && hipEventRecord(ev[2], hs) != hipSuccess) st = DDL_ERR_HIP;
+    if (hipStreamSynchronize(hs) != hipSuccess && st == DDL_OK) st = DDL_ERR_HIP;
+    float ms = 0.0f;
+    if (st == DDL_OK && reduce_ms) {
+        if (hipEventElapsedTime(&ms, ev[0], ev[1]) == hipSuccess) *reduce_ms = ms; else st = DDL_ERR_HIP;
+    }
+    if (st == DDL_OK && gather_ms) {
+        if (hipEventElapsedTime(&ms, ev[1], ev[2]) == hipSuccess) *gather_ms = ms; else st = DDL_ERR_HIP;
+    }
+    for (hipEvent_t e : ev)
         if (e) (void)hipEventDestroy(e);
     return st;
 }

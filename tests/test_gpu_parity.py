@@ -195,6 +195,12 @@ def test_side_stream_profile_entry_and_repeat(dev):
     assert len(ms) == 12 and all(x > 0 for x in ms)
     for j, g in enumerate(download(bufs)):
         assert_bitwise(g, want1[j], f"profile learner={j}")
+    say("timed entry")
+    bufs = upload(V, dev)
+    r_ms, g_ms = D.ddl_allreduce_sim_timed(bufs, P, plan, count, D.DDL_F32, torch.cuda.current_stream())
+    assert r_ms > 0 and g_ms > 0
+    for j, g in enumerate(download(bufs)):
+        assert_bitwise(g, want1[j], f"timed learner={j}")
 
 
 def test_buffers_as_aligned_views_of_one_allocation(dev):

@@ -123,7 +123,8 @@ def test_plan_argument_errors():
 
 
 @pytest.mark.parametrize("entry", [D.ddl_allreduce_sim, D.ddl_reduce_scatter_sim,
-                                   D.ddl_allgather_sim, D.ddl_allreduce_sim_profile])
+                                   D.ddl_allgather_sim, D.ddl_allreduce_sim_profile,
+                                   D.ddl_allreduce_sim_timed])
 def test_call_argument_errors(entry):
     count = 64
     plan = D.ddl_ring_plan([2, 2], 4, count)
@@ -148,6 +149,7 @@ def test_trivial_calls_need_no_device():
     plan0 = D.ddl_ring_plan([2, 2], 4, 0)
     D.ddl_allreduce_sim([0x100000 + 16 * j for j in range(4)], 4, plan0, 0)
     assert D.ddl_allreduce_sim_profile([0x100000 + 16 * j for j in range(4)], 4, plan0, 0) == [0.0] * 4
+    assert D.ddl_allreduce_sim_timed([0x100000 + 16 * j for j in range(4)], 4, plan0, 0) == (0.0, 0.0)
 
 
 # ---------------------------------------------------------------------------------------
