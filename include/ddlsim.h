@@ -174,6 +174,20 @@ ddl_status_t ddl_plan_owned_chunk(const ddl_plan_t* plan, int learner, size_t* o
  */
 double ddl_plan_model_time(const ddl_plan_t* plan, const double* bw, const double* lat);
 
+/*
+ * Choose the box for P learners with `bytes` per learner over m levels of links
+ * (Sec. 4.3: the dimensions are adjusted to the bandwidth and latency of the links so that
+ * the fastest links carry the most and the slowest link does not dominate).
+ *   bw[t], lat[t]  bandwidth (bytes/s) and per-phase latency (s) of dimension t
+ *   max_dim        NULL, or m caps on d_t (0 = no cap), e.g. the GPUs of one node for t = 0
+ * Every tuple (d_1..d_m) with d_t >= 1, product P and d_t <= max_dim[t] is scored with the
+ * estimate of ddl_plan_model_time; the smallest wins, exact ties go to the tuple that is
+ * smallest in lexicographic order.  dims_out: m ints; *time_out (may be NULL) the estimate.
+ * Host only.  DDL_ERR_DIMS if no tuple fits the caps, DDL_ERR_ARG for bad arguments.
+ */
+ddl_status_t ddl_choose_dims(int P, size_t bytes, int m, const double* bw, const double* lat,
+                             const int* max_dim, int* dims_out, double* time_out);
+
 /* Static, human-readable name of a status code. */
 const char* ddl_status_string(ddl_status_t status);
 

@@ -21,4 +21,5 @@ from .ddl_oracle import (  # noqa: F401
     sum_fp64,
     ring_time_model,
     multiring_time_model,
+    choose_dims_bruteforce,
 )

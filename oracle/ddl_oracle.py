@@ -301,3 +301,33 @@ def multiring_time_model(S: float, dims, B, L) -> float:
         T += 2.0 * ring_time_model(S_t, d, Bt, Lt)
         S_t /= d
     return T
+
+
+def choose_dims_bruteforce(P: int, S: float, B, L, max_dim=None):
+    """Every box (d_1..d_m), d_t >= 1, product P, within the caps, scored with
+    `multiring_time_model`; returns (best time, list of all boxes within 1e-12 of it).
+
+    Sec. 4.3 says only that the dimensions are adjusted to link bandwidths, topology and
+    latency; exhaustive search over the estimate is this build's reading (parity unpinned).
+    """
+    m = len(B)
+
+    def boxes(remaining, t):
+        """All (d_t..d_m) with product `remaining`."""
+        if t == m - 1:
+            yield (remaining,)
+            return
+        for d in range(1, remaining + 1):
+            if remaining % d == 0:
+                for rest in boxes(remaining // d, t + 1):
+                    yield (d,) + rest
+
+    scored = []
+    for dims in boxes(P, 0):
+        if max_dim is not None and any(c and d > c for d, c in zip(dims, max_dim)):
+            continue
+        scored.append((multiring_time_model(S, dims, B, L), dims))
+    if not scored:
+        return None, []
+    best = min(t for t, _ in scored)
+    return best, [list(d) for t, d in scored if t <= best * (1 + 1e-12)]

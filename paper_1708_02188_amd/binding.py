@@ -44,6 +44,9 @@ def _load():
         "ddl_plan_owned_chunk": (i, [vp, i, psz, psz]),
         "ddl_plan_model_time": (ctypes.c_double, [vp, ctypes.POINTER(ctypes.c_double),
                                                   ctypes.POINTER(ctypes.c_double)]),
+        "ddl_choose_dims": (i, [i, sz, i, ctypes.POINTER(ctypes.c_double),
+                                ctypes.POINTER(ctypes.c_double), pi, pi,
+                                ctypes.POINTER(ctypes.c_double)]),
         "ddl_status_string": (ctypes.c_char_p, [i]),
     }
     for name, (res, args) in sigs.items():
@@ -190,3 +193,15 @@ def ddl_plan_owned_chunk(plan, learner):
 def ddl_plan_model_time(plan, bw, lat):
     m = len(bw)
     return _lib.ddl_plan_model_time(_h(plan), (ctypes.c_double * m)(*bw), (ctypes.c_double * m)(*lat))
+
+
+def ddl_choose_dims(P, nbytes, bw, lat, max_dim=None):
+    """Returns (dims, modelled seconds)."""
+    m = len(bw)
+    dims = (ctypes.c_int * max(m, 1))()
+    t = ctypes.c_double(0.0)
+    caps = (ctypes.c_int * m)(*max_dim) if max_dim is not None else None
+    _check(_lib.ddl_choose_dims(P, nbytes, m, (ctypes.c_double * max(m, 1))(*bw),
+                                (ctypes.c_double * max(m, 1))(*lat), caps, dims, ctypes.byref(t)),
+           "ddl_choose_dims")
+    return list(dims)[:m], t.value

@@ -288,15 +288,15 @@ ddl_status_t ddl_plan_owned_chunk(const ddl_plan_t* plan, int learner, size_t* o
 
 double ddl_plan_model_time(const ddl_plan_t* plan, const double* bw, const double* lat) {
     if (plan == nullptr || bw == nullptr || lat == nullptr) return -1.0;
-    double level_bytes = double(plan->count) * plan->elem_size;
-    double total = 0.0;
-    for (size_t t = 0; t < plan->dims.size(); ++t) {
-        const int d = plan->dims[t];
+    const int m = static_cast<int>(plan->dims.size());
+    for (int t = 0; t < m; ++t)
         if (!(bw[t] > 0.0) || lat[t] < 0.0) return -1.0;
-        total += 2.0 * (d - 1) * (level_bytes / (d * bw[t]) + lat[t]);
-        level_bytes /= d;
-    }
-    return total;
+    return ddl::model_time(plan->dims.data(), m, double(plan->count) * plan->elem_size, bw, lat);
+}
+
+ddl_status_t ddl_choose_dims(int P, size_t bytes, int m, const double* bw, const double* lat,
+                             const int* max_dim, int* dims_out, double* time_out) {
+    return ddl::choose_dims(P, double(bytes), m, bw, lat, max_dim, dims_out, time_out);
 }
 
 const char* ddl_status_string(ddl_status_t status) {

@@ -91,4 +91,63 @@ void build_schedule(ddl_plan* plan) {
         for (int phase = 0; phase + 1 < plan->dims[t]; ++phase) emit(DDL_STEP_GATHER, t, phase);
 }
 
+double model_time(const int* dims, int m, double bytes, const double* bw, const double* lat) {
+    double level_bytes = bytes;
+    double total = 0.0;
+    for (int t = 0; t < m; ++t) {
+        const int d = dims[t];
+        total += 2.0 * (d - 1) * (level_bytes / (d * bw[t]) + lat[t]);
+        level_bytes /= d;
+    }
+    return total;
+}
+
+namespace {
+
+struct Search {
+    int P, m;
+    double bytes;
+    const double *bw, *lat;
+    const int* max_dim;
+    std::vector<int> cur, best;
+    double best_time = -1.0;
+
+    void visit(int t, int remaining) {
+        if (t == m - 1) {
+            if (max_dim && max_dim[t] > 0 && remaining > max_dim[t]) return;
+            cur[t] = remaining;
+            const double time = model_time(cur.data(), m, bytes, bw, lat);
+            // enumeration is in lexicographic order, so "<" keeps the first of equal scores
+            if (best_time < 0.0 || time < best_time) {
+                best_time = time;
+                best = cur;
+            }
+            return;
+        }
+        for (int d = 1; d <= remaining; ++d) {
+            if (remaining % d != 0) continue;
+            if (max_dim && max_dim[t] > 0 && d > max_dim[t]) break;
+            cur[t] = d;
+            visit(t + 1, remaining / d);
+        }
+    }
+};
+
+}  // namespace
+
+ddl_status_t choose_dims(int P, double bytes, int m, const double* bw, const double* lat,
+                         const int* max_dim, int* dims_out, double* time_out) {
+    if (P < 1 || P > DDL_MAX_LEARNERS || bw == nullptr || lat == nullptr || dims_out == nullptr)
+        return DDL_ERR_ARG;
+    if (m < 1 || m > DDL_MAX_DIMS) return DDL_ERR_DIMS;
+    for (int t = 0; t < m; ++t)
+        if (!(bw[t] > 0.0) || !(lat[t] >= 0.0) || (max_dim && max_dim[t] < 0)) return DDL_ERR_ARG;
+    Search s{P, m, bytes, bw, lat, max_dim, std::vector<int>(m, 1), {}, -1.0};
+    s.visit(0, P);
+    if (s.best.empty()) return DDL_ERR_DIMS;
+    for (int t = 0; t < m; ++t) dims_out[t] = s.best[t];
+    if (time_out) *time_out = s.best_time;
+    return DDL_OK;
+}
+
 }  // namespace ddl

@@ -75,4 +75,12 @@ void build_schedule(ddl_plan* plan);
 
 ddl_status_t validate_dims(const int* dims, int m, int P);
 
+// Estimated cluster time of reduction + distribution for a box (Sec. 4.3 ring estimate per
+// dimension, on the bytes left at that level).
+double model_time(const int* dims, int m, double bytes, const double* bw, const double* lat);
+
+// Exhaustive search over boxes; see ddl_choose_dims.
+ddl_status_t choose_dims(int P, double bytes, int m, const double* bw, const double* lat,
+                         const int* max_dim, int* dims_out, double* time_out);
+
 }  // namespace ddl

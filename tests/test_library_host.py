@@ -217,3 +217,35 @@ def test_workload_shapes_match_the_paper_sizes():
     assert abs(4 * I.RESNET101_22K_COUNT - fig["resnet101_22k_bytes"]) / fig["resnet101_22k_bytes"] < 0.01
     for cfg in I.CONFIGS:
         assert prod(cfg["dims"]) == cfg["P"]
+
+
+# ---------------------------------------------------------------------------------------
+# dimension chooser
+# ---------------------------------------------------------------------------------------
+def test_choose_dims_matches_bruteforce_oracle():
+    fig = read_golden_kv("paper_figures.txt")
+    bw = [fig["bw_dim1"], fig["bw_dim2"], fig["bw_dim3"]]
+    cases = [
+        (256, 349e6, bw, [0.0] * 3, None),
+        (256, 349e6, bw, [5e-5] * 3, None),
+        (256, 349e6, bw, [5e-5] * 3, [4, 16, 0]),
+        (256, 349e6, bw, [0.0] * 3, [4, 16, 4]),
+        (64, 1e8, bw, [1e-5, 2e-5, 1e-4], [4, 0, 0]),
+        (60, 1e6, [1e10, 5e9], [1e-6, 1e-3], None),
+        (97, 1e6, [1e10, 5e9, 1e9], [1e-6] * 3, None),
+        (1, 1e6, [1e10], [0.0], None),
+        (256, 1.0, [1e10] * 8, [1.0] * 8, None),
+    ]
+    for P, S, B, L, caps in cases:
+        dims, t = D.ddl_choose_dims(P, int(S), B, L, caps)
+        best, boxes = O.choose_dims_bruteforce(P, float(int(S)), B, L, caps)
+        assert prod(dims) == P and dims in boxes, (P, dims, boxes)
+        assert t == pytest.approx(best, rel=1e-12)
+        plan = D.ddl_ring_plan(dims, P, int(S) // 4)
+        assert D.ddl_plan_model_time(plan, B, L) == pytest.approx(t, rel=1e-6)
+    # exact ties go to the lexicographically smallest box
+    assert D.ddl_choose_dims(64, 10 ** 6, [1e10] * 3, [0.0] * 3)[0] == [1, 1, 64]
+    assert status_of(D.ddl_choose_dims, 256, 100, bw, [0.0] * 3, [4, 4, 4]) == D.DDL_ERR_DIMS
+    assert status_of(D.ddl_choose_dims, 0, 100, bw, [0.0] * 3) == D.DDL_ERR_ARG
+    assert status_of(D.ddl_choose_dims, 4, 100, [0.0], [0.0]) == D.DDL_ERR_ARG
+    assert status_of(D.ddl_choose_dims, 4, 100, [1.0], [-1.0]) == D.DDL_ERR_ARG

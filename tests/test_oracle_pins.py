@@ -546,3 +546,25 @@ def test_fold_range_equals_whole_fold():
     for lo, hi in [(0, 0), (0, 1), (5, 900), (998, 1003), (83, 84), (0, 1003)]:
         part = O.allreduce_fold_range(lambda r, a, b: V[r][a:b], dims, count, lo, hi, np.float32)
         assert part.tobytes() == whole[lo:hi].tobytes()
+
+
+def test_choose_dims_bruteforce_special_cases():
+    S = 349e6
+    # no latency, one bandwidth: every box moves the same bytes -> all tie at 2 S (1 - 1/P) / B
+    t, boxes = O.choose_dims_bruteforce(64, S, [1e10] * 3, [0.0] * 3)
+    assert t == pytest.approx(2 * S * (1 - 1 / 64) / 1e10, rel=1e-12)
+    assert [4, 4, 4] in boxes and [64, 1, 1] in boxes and [1, 8, 8] in boxes and len(boxes) == 28
+    # one level: only the flat ring
+    assert O.choose_dims_bruteforce(12, S, [1e10], [1e-5])[1] == [[12]]
+    # latency dominates: the box with the fewest phases, sum(d_t - 1) minimal
+    t, boxes = O.choose_dims_bruteforce(256, 1.0, [1e10] * 3, [1.0] * 3)
+    assert sorted(boxes) == [[4, 8, 8], [8, 4, 8], [8, 8, 4]]
+    assert t == pytest.approx(2 * 17 * 1.0, rel=1e-6)
+    assert O.choose_dims_bruteforce(256, 1.0, [1e10] * 8, [1.0] * 8)[1] == [[2] * 8]
+    # bandwidth only, faster first level: everything rides the fastest links (Sec. 4.3)
+    fig = read_golden_kv("paper_figures.txt")
+    bw = [fig["bw_dim1"], fig["bw_dim2"], fig["bw_dim3"]]
+    assert O.choose_dims_bruteforce(256, S, bw, [0.0] * 3)[1] == [[256, 1, 1]]
+    # the paper's cluster: 4 GPUs per node, 16 nodes per rack, 4 racks leave one box
+    assert O.choose_dims_bruteforce(256, S, bw, [0.0] * 3, [4, 16, 4])[1] == [[4, 16, 4]]
+    assert O.choose_dims_bruteforce(256, S, bw, [0.0] * 3, [4, 4, 4]) == (None, [])
