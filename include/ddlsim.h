@@ -38,12 +38,16 @@ extern "C" {
 /* Opaque schedule; created by ddl_ring_plan, owned by the library, freed by ddl_plan_free. */
 typedef struct ddl_plan ddl_plan_t;
 
-/* Element types.  Sums are formed in the element type itself, one rounding per addition
- * (the paper speaks of "floating point entries" of 4 bytes: 90 M entries = 350 MB). */
+/* Element types.  Sums are formed in the element type itself, one rounding per addition,
+ * round-to-nearest-even (the paper speaks of "floating point entries" of 4 bytes: 90 M
+ * entries = 350 MB).  The 16-bit types are added in binary32 and rounded once to 16 bits,
+ * which equals the correctly rounded 16-bit sum. */
 typedef enum {
     DDL_F32 = 0,
     DDL_F64 = 1,
-    DDL_I32 = 2
+    DDL_I32 = 2,  /* two's complement, wraps */
+    DDL_F16 = 3,  /* IEEE binary16 */
+    DDL_BF16 = 4  /* bfloat16: the upper 16 bits of a binary32 */
 } ddl_dtype_t;
 
 typedef enum {

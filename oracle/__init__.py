@@ -19,6 +19,9 @@ from .ddl_oracle import (  # noqa: F401
     allreduce_fold,
     allreduce_fold_range,
     sum_fp64,
+    bf16_add,
+    bf16_to_f32,
+    f32_to_bf16,
     ring_time_model,
     multiring_time_model,
     choose_dims_bruteforce,

@@ -187,38 +187,44 @@ def _check_inputs(V, dims):
     return P, count
 
 
-def _run(bufs, steps):
+def _plain_add(x, y):
+    return x + y
+
+
+def _run(bufs, steps, add=None):
+    add = add or _plain_add
     for kind, _, ops in steps:
         # A phase is N concurrent transfers: every message leaves its sender
         # before any message is applied at a receiver.
         messages = [bufs[src][a:b].copy() for src, _, a, b in ops]
         for (_, dst, a, b), msg in zip(ops, messages):
             if kind == "RS":
-                bufs[dst][a:b] = bufs[dst][a:b] + msg  # one rounding per element
+                bufs[dst][a:b] = add(bufs[dst][a:b], msg)  # one rounding per element
             else:
                 bufs[dst][a:b] = msg
     return bufs
 
 
-def allreduce_steps(V, dims) -> list:
+def allreduce_steps(V, dims, add=None) -> list:
     """Form (i): simulate every phase on in-memory copies of the P buffers.
 
     Returns the P buffers after reduce-scatter and all-gather (Sec. 4.1, 4.3);
-    each must hold R = sum_j V_j.
+    each must hold R = sum_j V_j.  `add(x, y)` replaces numpy's `+` for element
+    types numpy cannot add itself (see `bf16_add`).
     """
     _, count = _check_inputs(V, dims)
     bufs = [np.array(v, copy=True) for v in V]
-    return _run(bufs, schedule(dims, count, granule(bufs[0].dtype)))
+    return _run(bufs, schedule(dims, count, granule(bufs[0].dtype)), add)
 
 
-def reduce_scatter_steps(V, dims) -> list:
+def reduce_scatter_steps(V, dims, add=None) -> list:
     """Only the reduce-scatter half (Sec. 4.1 ReduceScatter): afterwards learner
     with coordinates k holds the completed finest chunk k; the rest of each buffer
     holds partial sums."""
     _, count = _check_inputs(V, dims)
     bufs = [np.array(v, copy=True) for v in V]
     steps = [s for s in schedule(dims, count, granule(bufs[0].dtype)) if s[0] == "RS"]
-    return _run(bufs, steps)
+    return _run(bufs, steps, add)
 
 
 def allgather_steps(V, dims) -> list:
@@ -230,7 +236,7 @@ def allgather_steps(V, dims) -> list:
     return _run(bufs, steps)
 
 
-def allreduce_fold_range(get, dims, count: int, lo: int, hi: int, dtype) -> np.ndarray:
+def allreduce_fold_range(get, dims, count: int, lo: int, hi: int, dtype, add=None) -> np.ndarray:
     """Form (ii): the result on elements [lo, hi) only, element by element, without
     simulating phases.  `get(r, a, b)` returns elements [a, b) of learner r's input.
 
@@ -240,6 +246,7 @@ def allreduce_fold_range(get, dims, count: int, lo: int, hi: int, dtype) -> np.n
     chunk's owner and travels once round the ring until it reaches the owner.
     Dimension 1 is folded first, then dimension 2 over those results, and so on.
     """
+    add = add or _plain_add
     m = len(dims)
     out = np.empty(hi - lo, dtype=dtype)
     for k, ca, cb in fine_chunks(dims, count, granule(dtype)):
@@ -254,17 +261,41 @@ def allreduce_fold_range(get, dims, count: int, lo: int, hi: int, dtype) -> np.n
             for rest in itertools.product(*[range(dd) for dd in dims[t + 1:]]):
                 acc = A[((k[t] + 1) % d,) + rest]
                 for i in range(2, d + 1):
-                    acc = acc + A[((k[t] + i) % d,) + rest]
+                    acc = add(acc, A[((k[t] + i) % d,) + rest])
                 nxt[rest] = acc
             A = nxt
         out[a - lo:b - lo] = A[()]
     return out
 
 
-def allreduce_fold(V, dims) -> np.ndarray:
+def allreduce_fold(V, dims, add=None) -> np.ndarray:
     """Form (ii) over whole in-memory buffers: the single vector every learner ends with."""
     _, count = _check_inputs(V, dims)
-    return allreduce_fold_range(lambda r, a, b: V[r][a:b], dims, count, 0, count, V[0].dtype)
+    return allreduce_fold_range(lambda r, a, b: V[r][a:b], dims, count, 0, count, V[0].dtype, add)
+
+
+# --------------------------------------------------------------------------------------
+# bfloat16, which numpy has no type for: stored as uint16 = the upper half of a float32
+# --------------------------------------------------------------------------------------
+def bf16_to_f32(x: np.ndarray) -> np.ndarray:
+    """Widen bfloat16 bit patterns (uint16) to float32: exact."""
+    return (x.astype(np.uint32) << np.uint32(16)).view(np.float32)
+
+
+def f32_to_bf16(f: np.ndarray) -> np.ndarray:
+    """Round float32 to the nearest bfloat16 bit pattern, ties to the even mantissa."""
+    w = np.ascontiguousarray(f, dtype=np.float32).view(np.uint32).astype(np.uint64)
+    lsb = (w >> np.uint64(16)) & np.uint64(1)
+    rounded = ((w + np.uint64(0x7FFF) + lsb) >> np.uint64(16)).astype(np.uint16)
+    nan = (w & np.uint64(0x7FFFFFFF)) > np.uint64(0x7F800000)
+    return np.where(nan, ((w >> np.uint64(16)) | np.uint64(0x40)).astype(np.uint16), rounded)
+
+
+def bf16_add(x: np.ndarray, y: np.ndarray) -> np.ndarray:
+    """x + y in bfloat16 (uint16 bit patterns): added in float32, rounded once to
+    bfloat16.  float32 keeps 24 >= 2*8 + 2 significand bits, so the two roundings equal
+    one correctly rounded bfloat16 addition."""
+    return f32_to_bf16(bf16_to_f32(x) + bf16_to_f32(y))
 
 
 def sum_fp64(V) -> np.ndarray:

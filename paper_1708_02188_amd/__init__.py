@@ -9,7 +9,7 @@ build module itself can be run from a tree whose library is missing or stale.
 import importlib
 
 _BINDING_NAMES = (
-    "DDL_F32", "DDL_F64", "DDL_I32",
+    "DDL_F32", "DDL_F64", "DDL_I32", "DDL_F16", "DDL_BF16",
     "DDL_OK", "DDL_ERR_ARG", "DDL_ERR_DIMS", "DDL_ERR_DTYPE", "DDL_ERR_ALIGN",
     "DDL_ERR_PLAN_MISMATCH", "DDL_ERR_NOMEM", "DDL_ERR_HIP",
     "DDL_STEP_REDUCE", "DDL_STEP_GATHER",

@@ -4,7 +4,7 @@ import os
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
 
-DDL_F32, DDL_F64, DDL_I32 = 0, 1, 2
+DDL_F32, DDL_F64, DDL_I32, DDL_F16, DDL_BF16 = 0, 1, 2, 3, 4
 DDL_OK = 0
 DDL_ERR_ARG, DDL_ERR_DIMS, DDL_ERR_DTYPE, DDL_ERR_ALIGN = -1, -2, -3, -4
 DDL_ERR_PLAN_MISMATCH, DDL_ERR_NOMEM, DDL_ERR_HIP = -5, -6, -7

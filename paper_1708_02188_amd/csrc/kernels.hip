@@ -47,11 +47,54 @@
 namespace ddl {
 namespace {
 
-template <typename T> struct Vec16;
-template <> struct Vec16<float>  { typedef float  type __attribute__((ext_vector_type(4))); };
-template <> struct Vec16<double> { typedef double type __attribute__((ext_vector_type(2))); };
+// Element traits: the 16-byte vector a lane moves, and the sum of two vectors / elements.
+template <typename T> struct Elem;
+template <> struct Elem<float> {
+    typedef float S;
+    typedef float V __attribute__((ext_vector_type(4)));
+    static __device__ __forceinline__ V add(V a, V b) { return a + b; }
+    static __device__ __forceinline__ S add1(S a, S b) { return a + b; }
+};
+template <> struct Elem<double> {
+    typedef double S;
+    typedef double V __attribute__((ext_vector_type(2)));
+    static __device__ __forceinline__ V add(V a, V b) { return a + b; }
+    static __device__ __forceinline__ S add1(S a, S b) { return a + b; }
+};
 // 32-bit integers are summed as unsigned: wrap-around, the same bits as two's complement
-template <> struct Vec16<unsigned> { typedef unsigned type __attribute__((ext_vector_type(4))); };
+template <> struct Elem<unsigned> {
+    typedef unsigned S;
+    typedef unsigned V __attribute__((ext_vector_type(4)));
+    static __device__ __forceinline__ V add(V a, V b) { return a + b; }
+    static __device__ __forceinline__ S add1(S a, S b) { return a + b; }
+};
+template <> struct Elem<_Float16> {
+    typedef _Float16 S;
+    typedef _Float16 V __attribute__((ext_vector_type(8)));
+    static __device__ __forceinline__ V add(V a, V b) { return a + b; }
+    static __device__ __forceinline__ S add1(S a, S b) { return a + b; }
+};
+// bfloat16 travels as its 16 raw bits; widened to binary32 (exact), added there, and
+// rounded back to the nearest bfloat16, ties to even.
+struct bf16_bits {
+    unsigned short u;
+};
+template <> struct Elem<bf16_bits> {
+    typedef unsigned short S;
+    typedef unsigned short V __attribute__((ext_vector_type(8)));
+    static __device__ __forceinline__ S add1(S a, S b) {
+        const float f = __uint_as_float(unsigned(a) << 16) + __uint_as_float(unsigned(b) << 16);
+        const unsigned w = __float_as_uint(f);
+        if ((w & 0x7FFFFFFFu) > 0x7F800000u) return S((w >> 16) | 0x0040u);  // NaN stays NaN
+        return S((w + 0x7FFFu + ((w >> 16) & 1u)) >> 16);
+    }
+    static __device__ __forceinline__ V add(V a, V b) {
+        V r;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) r[i] = add1(a[i], b[i]);
+        return r;
+    }
+};
 
 // Pointers are tagged as global memory so the loads and stores are global_* rather than
 // flat_* instructions (no aperture check, no LDS counter involvement).
@@ -101,8 +144,9 @@ constexpr uint64_t kRowVecs = kRowBytes / 16;
 template <typename T, bool REDUCE>
 __global__ __launch_bounds__(DDL_THREADS) void step_kernel(const ResolvedOp* __restrict__ rops,
                                                            unsigned tile_stride) {
-    typedef typename Vec16<T>::type V;
-    constexpr int64_t VL = 16 / sizeof(T);                          // elements per vector
+    typedef typename Elem<T>::V V;
+    typedef typename Elem<T>::S S;
+    constexpr int64_t VL = 16 / sizeof(S);                          // elements per vector
     constexpr int64_t TILE = int64_t(DDL_THREADS) * DDL_UNROLL;     // vectors per tile
 
     // the whole record in one scalar load: {src address, dst address, n, -}
@@ -127,7 +171,7 @@ __global__ __launch_bounds__(DDL_THREADS) void step_kernel(const ResolvedOp* __r
 #pragma unroll
                 for (int u = 0; u < DDL_UNROLL; ++u) b[u] = stream_load(d + u * DDL_THREADS);
 #pragma unroll
-                for (int u = 0; u < DDL_UNROLL; ++u) a[u] = b[u] + a[u];
+                for (int u = 0; u < DDL_UNROLL; ++u) a[u] = Elem<T>::add(b[u], a[u]);
             }
 #pragma unroll
             for (int u = 0; u < DDL_UNROLL; ++u) stream_store(d + u * DDL_THREADS, a[u]);
@@ -138,15 +182,15 @@ __global__ __launch_bounds__(DDL_THREADS) void step_kernel(const ResolvedOp* __r
                 const int64_t v = first + u * DDL_THREADS + tid;
                 if (v >= 0 && v < nv) {
                     V a = src[v];
-                    if (REDUCE) a = dst[v] + a;
+                    if (REDUCE) a = Elem<T>::add(dst[v], a);
                     dst[v] = a;
                 } else if (v == nv) {
                     // the buffer's last, short vector: element by element
-                    const DDL_GLOBAL T* se = (const DDL_GLOBAL T*)(src + nv);
-                    DDL_GLOBAL T* de = (DDL_GLOBAL T*)(dst + nv);
+                    const DDL_GLOBAL S* se = (const DDL_GLOBAL S*)(src + nv);
+                    DDL_GLOBAL S* de = (DDL_GLOBAL S*)(dst + nv);
                     for (int64_t e = 0; e < n - nv * VL; ++e) {
-                        T a = se[e];
-                        if (REDUCE) a = de[e] + a;
+                        S a = se[e];
+                        if (REDUCE) a = Elem<T>::add1(de[e], a);
                         de[e] = a;
                     }
                 }
@@ -158,7 +202,7 @@ __global__ __launch_bounds__(DDL_THREADS) void step_kernel(const ResolvedOp* __r
 template <typename T>
 hipError_t launch_typed(const ddl_plan& plan, const Step& step, const ResolvedOp* d_rops,
                         hipStream_t stream) {
-    constexpr uint64_t VL = 16 / sizeof(T);
+    constexpr uint64_t VL = 16 / sizeof(typename Elem<T>::S);
     constexpr uint64_t TILE = uint64_t(DDL_THREADS) * DDL_UNROLL;  // vectors
     // slots to cover: the whole vectors, one for a short last vector, and the row shift
     uint64_t tiles = (step.max_n / VL + 1 + (kRowVecs - 1) + TILE - 1) / TILE;
@@ -192,6 +236,8 @@ hipError_t launch_step(const ddl_plan& plan, const Step& step, const ResolvedOp*
         case DDL_F32: return launch_typed<float>(plan, step, d_rops, stream);
         case DDL_F64: return launch_typed<double>(plan, step, d_rops, stream);
         case DDL_I32: return launch_typed<unsigned>(plan, step, d_rops, stream);
+        case DDL_F16: return launch_typed<_Float16>(plan, step, d_rops, stream);
+        case DDL_BF16: return launch_typed<bf16_bits>(plan, step, d_rops, stream);
     }
     return hipErrorInvalidValue;
 }

@@ -10,6 +10,8 @@ int dtype_size(ddl_dtype_t dtype) {
         case DDL_F32: return 4;
         case DDL_F64: return 8;
         case DDL_I32: return 4;
+        case DDL_F16: return 2;
+        case DDL_BF16: return 2;
     }
     return 0;
 }

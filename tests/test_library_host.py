@@ -46,7 +46,8 @@ PLAN_CASES = [
 
 
 @pytest.mark.parametrize("dims,count", PLAN_CASES)
-@pytest.mark.parametrize("dtype,itemsize", [(D.DDL_F32, 4), (D.DDL_F64, 8), (D.DDL_I32, 4)])
+@pytest.mark.parametrize("dtype,itemsize", [(D.DDL_F32, 4), (D.DDL_F64, 8), (D.DDL_I32, 4),
+                                            (D.DDL_F16, 2), (D.DDL_BF16, 2)])
 def test_plan_tables_equal_oracle_schedule(dims, count, dtype, itemsize):
     P = prod(dims)
     plan = D.ddl_ring_plan(dims, P, count, dtype)

@@ -490,7 +490,7 @@ def test_mutation_dropped_phase(monkeypatch):
 
 
 def test_mutation_copy_instead_of_add(monkeypatch):
-    def run_copy_only(bufs, steps):
+    def run_copy_only(bufs, steps, add=None):
         for _, _, ops in steps:
             msgs = [bufs[src][a:b].copy() for src, _, a, b in ops]
             for (_, dst, a, b), msg in zip(ops, msgs):
@@ -568,3 +568,53 @@ def test_choose_dims_bruteforce_special_cases():
     # the paper's cluster: 4 GPUs per node, 16 nodes per rack, 4 racks leave one box
     assert O.choose_dims_bruteforce(256, S, bw, [0.0] * 3, [4, 16, 4])[1] == [[4, 16, 4]]
     assert O.choose_dims_bruteforce(256, S, bw, [0.0] * 3, [4, 4, 4]) == (None, [])
+
+
+# ---------------------------------------------------------------------------------------
+# 16-bit element types
+# ---------------------------------------------------------------------------------------
+def test_bf16_helpers_against_torch_cpu():
+    import torch
+    rng = np.random.default_rng(14)
+    f = np.concatenate([
+        (rng.uniform(-1, 1, 20000) * 10.0 ** rng.uniform(-30, 30, 20000)).astype(np.float32),
+        np.array([0.0, -0.0, 1.0, 1.00390625, 1.01171875, 3.3895314e38, 1e-40, np.inf, -np.inf], np.float32),
+    ])
+    bits = O.f32_to_bf16(f)
+    want = torch.from_numpy(f).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    assert np.array_equal(bits, want)
+    back = torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).to(torch.float32).numpy()
+    assert O.bf16_to_f32(bits).tobytes() == back.tobytes()
+    x, y = bits[:10000], bits[10000:20000]
+    tsum = (torch.from_numpy(x.view(np.int16)).view(torch.bfloat16) +
+            torch.from_numpy(y.view(np.int16)).view(torch.bfloat16)).view(torch.int16).numpy().view(np.uint16)
+    assert np.array_equal(O.bf16_add(x, y), tsum)
+    # ties go to the even mantissa: 1 + 2^-8 lies between 1 and 1 + 2^-7
+    assert O.f32_to_bf16(np.array([1.00390625], np.float32))[0] == 0x3F80
+    assert O.f32_to_bf16(np.array([1.01171875], np.float32))[0] == 0x3F82
+    assert np.isnan(O.bf16_to_f32(O.f32_to_bf16(np.array([np.nan], np.float32))))[0]
+
+
+def test_sixteen_bit_types_bruteforce_and_forms_agree():
+    rng = np.random.default_rng(15)
+    for dims in ([4], [2, 3], [4, 2, 2]):
+        P = prod(dims)
+        for count in (0, 7, 8, 9, 100, 1001):
+            # small integers are exact in both 16-bit types -> plain integer sum
+            ints = [rng.integers(-8, 9, count) for _ in range(P)]
+            want = sum(ints) if count else np.zeros(0)
+            h = O.allreduce_steps([v.astype(np.float16) for v in ints], dims)
+            b = O.allreduce_steps([O.f32_to_bf16(v.astype(np.float32)) for v in ints], dims, add=O.bf16_add)
+            for j in range(P):
+                assert np.array_equal(h[j].astype(np.int64), want)
+                assert np.array_equal(O.bf16_to_f32(b[j]).astype(np.int64), want)
+            # general values: simulator == fold, in each type's own arithmetic
+            V = wide_fp32_inputs(rng, P, count)
+            Vh = [v.astype(np.float16) for v in V]
+            Vb = [O.f32_to_bf16(v) for v in V]
+            for g in O.allreduce_steps(Vh, dims):
+                assert g.tobytes() == O.allreduce_fold(Vh, dims).tobytes()
+            for g in O.allreduce_steps(Vb, dims, add=O.bf16_add):
+                assert g.tobytes() == O.allreduce_fold(Vb, dims, add=O.bf16_add).tobytes()
+    # chunks are cut on 16-byte granules = 8 elements
+    assert O.granule(np.float16) == 8 and O.granule(np.uint16) == 8
