@@ -31,6 +31,7 @@ def main():
                     help="HBM budget for distinct input sets (one per step until it is used up)")
     ap.add_argument("--profile-passes", type=int, default=10)
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
+    ap.add_argument("--no-fused", action="store_true", help="skip timing the step-fused variant")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="also run one plain device-to-device copy of this many MiB (a dispatch of "
                          "known size, to scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
@@ -87,6 +88,28 @@ def main():
     ms_per_step = elapsed * 1e3 / K
     per_learner_gbs = 4 * count / (ms_per_step * 1e-3) / 1e9
     hbm_gbs = bytes_total / (ms_per_step * 1e-3) / 1e9
+
+    # The step-fused variant of the same allreduce (one pass, 8*count*P bytes), rated
+    # against its own byte count; reported beside the schedule's figures, never as `value`.
+    fused = None
+    if not args.no_fused:
+        try:
+            for i in range(W):
+                D.ddl_allreduce_fused_sim(sets[i % n_sets], P, plan, count, D.DDL_F32, stream)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for i in range(W, W + K):
+                D.ddl_allreduce_fused_sim(sets[i % n_sets], P, plan, count, D.DDL_F32, stream)
+            torch.cuda.synchronize()
+            f_ms = (time.perf_counter() - t0) * 1e3 / K
+            f_bytes = D.ddl_plan_fused_bytes(plan)
+            fused = {"entry": "ddl_allreduce_fused_sim", "ms_per_step": f_ms,
+                     "GBs_per_virtual_learner": 4 * count / (f_ms * 1e-3) / 1e9,
+                     "bytes": f_bytes, "achieved_GBs": f_bytes / (f_ms * 1e-3) / 1e9,
+                     "frac": f_bytes / (f_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                     "speedup_vs_schedule": ms_per_step / f_ms}
+        except D.DdlError as e:
+            fused = {"entry": "ddl_allreduce_fused_sim", "error": str(e)}
 
     # quick self-check on the last set used: every learner holds the same bits
     last = sets[(W + K - 1) % n_sets]
@@ -187,6 +210,7 @@ def main():
         "hbm_GBs": hbm_gbs, "hbm_frac_of_peak": hbm_gbs / HBM_PEAK_GBS,
         "learners_identical": bool(same),
         "roofline": roofline,
+        "fused_variant": fused,
         "cpu_baseline": cpu,
     }
     print(json.dumps(out))

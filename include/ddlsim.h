@@ -58,7 +58,8 @@ typedef enum {
     DDL_ERR_ALIGN = -4,         /* a learner buffer is not 16-byte aligned                  */
     DDL_ERR_PLAN_MISMATCH = -5, /* P / count / dtype differ from what the plan was made for */
     DDL_ERR_NOMEM = -6,         /* host or device allocation failed                         */
-    DDL_ERR_HIP = -7            /* a HIP runtime call failed (no device, launch error, ...) */
+    DDL_ERR_HIP = -7,           /* a HIP runtime call failed (no device, launch error, ...) */
+    DDL_ERR_UNSUPPORTED = -8    /* valid arguments this entry point does not serve          */
 } ddl_status_t;
 
 enum { DDL_STEP_REDUCE = 0, DDL_STEP_GATHER = 1 };
@@ -140,6 +141,23 @@ ddl_status_t ddl_allreduce_sim_timed(void** bufs, int P, const ddl_plan_t* plan,
                                      ddl_dtype_t dtype, void* stream, float* reduce_ms,
                                      float* gather_ms);
 
+/*
+ * Step-fused allreduce: the same final state as ddl_allreduce_sim (every learner holds the
+ * sum, bit for bit the value the schedule's summation order gives) produced in ONE pass
+ * that reads every learner's element once, folds the ring orders of all dimensions in
+ * registers and writes the result to every learner, instead of executing the phases one
+ * by one.  The partial sums the phases would have left in the buffers on the way are never
+ * materialised.  Memory traffic is 2 * sizeof(element) * count * P bytes
+ * (ddl_plan_fused_bytes) instead of ddl_plan_bytes_moved.
+ * Same arguments, rules and errors as ddl_allreduce_sim; additionally
+ * DDL_ERR_UNSUPPORTED if P > DDL_FUSED_MAX_LEARNERS or the box has more than
+ * DDL_FUSED_MAX_LEVELS dimensions of size > 1 (use ddl_allreduce_sim then).
+ */
+#define DDL_FUSED_MAX_LEARNERS 1024
+#define DDL_FUSED_MAX_LEVELS 4
+ddl_status_t ddl_allreduce_fused_sim(void** bufs, int P, const ddl_plan_t* plan, size_t count,
+                                     ddl_dtype_t dtype, void* stream);
+
 /* ---- plan introspection (host only) ------------------------------------------------ */
 
 /* 2 * sum_t (d_t - 1): Sec. 4.3, d-1 phases per ring, once reducing and once gathering.
@@ -154,7 +172,11 @@ int ddl_plan_num_learners(const ddl_plan_t* plan);
  * Equals 5 * sizeof(element) * count * (P - 1) when count is a multiple of G * P. */
 size_t ddl_plan_bytes_moved(const ddl_plan_t* plan);
 
-/* The same for one step; 0 for a bad index. */
+/* Bytes ddl_allreduce_fused_sim moves: every element of every learner read once and
+ * written once. */
+size_t ddl_plan_fused_bytes(const ddl_plan_t* plan);
+
+/* ddl_plan_bytes_moved for one step; 0 for a bad index. */
 size_t ddl_plan_step_bytes(const ddl_plan_t* plan, int step);
 
 /*

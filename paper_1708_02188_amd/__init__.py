@@ -11,12 +11,13 @@ import importlib
 _BINDING_NAMES = (
     "DDL_F32", "DDL_F64", "DDL_I32", "DDL_F16", "DDL_BF16",
     "DDL_OK", "DDL_ERR_ARG", "DDL_ERR_DIMS", "DDL_ERR_DTYPE", "DDL_ERR_ALIGN",
-    "DDL_ERR_PLAN_MISMATCH", "DDL_ERR_NOMEM", "DDL_ERR_HIP",
+    "DDL_ERR_PLAN_MISMATCH", "DDL_ERR_NOMEM", "DDL_ERR_HIP", "DDL_ERR_UNSUPPORTED",
     "DDL_STEP_REDUCE", "DDL_STEP_GATHER",
     "DdlError", "Plan",
     "ddl_ring_plan", "ddl_plan_free", "ddl_plan_prepare",
     "ddl_allreduce_sim", "ddl_reduce_scatter_sim", "ddl_allgather_sim",
-    "ddl_allreduce_sim_profile", "ddl_allreduce_sim_timed",
+    "ddl_allreduce_sim_profile", "ddl_allreduce_sim_timed", "ddl_allreduce_fused_sim",
+    "ddl_plan_fused_bytes",
     "ddl_plan_num_steps", "ddl_plan_num_learners", "ddl_plan_bytes_moved", "ddl_plan_step_bytes",
     "ddl_plan_get_step", "ddl_plan_owned_chunk", "ddl_plan_model_time", "ddl_choose_dims", "ddl_status_string",
     "library_path",

@@ -7,7 +7,7 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 DDL_F32, DDL_F64, DDL_I32, DDL_F16, DDL_BF16 = 0, 1, 2, 3, 4
 DDL_OK = 0
 DDL_ERR_ARG, DDL_ERR_DIMS, DDL_ERR_DTYPE, DDL_ERR_ALIGN = -1, -2, -3, -4
-DDL_ERR_PLAN_MISMATCH, DDL_ERR_NOMEM, DDL_ERR_HIP = -5, -6, -7
+DDL_ERR_PLAN_MISMATCH, DDL_ERR_NOMEM, DDL_ERR_HIP, DDL_ERR_UNSUPPORTED = -5, -6, -7, -8
 DDL_STEP_REDUCE, DDL_STEP_GATHER = 0, 1
 
 
@@ -33,6 +33,8 @@ def _load():
         "ddl_allreduce_sim": (i, sim_args),
         "ddl_reduce_scatter_sim": (i, sim_args),
         "ddl_allgather_sim": (i, sim_args),
+        "ddl_allreduce_fused_sim": (i, sim_args),
+        "ddl_plan_fused_bytes": (sz, [vp]),
         "ddl_allreduce_sim_profile": (i, sim_args + [ctypes.POINTER(ctypes.c_float)]),
         "ddl_allreduce_sim_timed": (i, sim_args + [ctypes.POINTER(ctypes.c_float),
                                                    ctypes.POINTER(ctypes.c_float)]),
@@ -137,6 +139,15 @@ def ddl_reduce_scatter_sim(bufs, P, plan, count, dtype=DDL_F32, stream=None):
 def ddl_allgather_sim(bufs, P, plan, count, dtype=DDL_F32, stream=None):
     _check(_lib.ddl_allgather_sim(_ptr_array(bufs), P, _h(plan), count, dtype, _stream(stream)),
            "ddl_allgather_sim")
+
+
+def ddl_allreduce_fused_sim(bufs, P, plan, count, dtype=DDL_F32, stream=None):
+    _check(_lib.ddl_allreduce_fused_sim(_ptr_array(bufs), P, _h(plan), count, dtype, _stream(stream)),
+           "ddl_allreduce_fused_sim")
+
+
+def ddl_plan_fused_bytes(plan):
+    return _lib.ddl_plan_fused_bytes(_h(plan))
 
 
 def ddl_allreduce_sim_profile(bufs, P, plan, count, dtype=DDL_F32, stream=None):

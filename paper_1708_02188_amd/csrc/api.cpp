@@ -57,6 +57,49 @@ ddl_status_t device_tables(const ddl_plan* plan, DeviceTables* out) {
     return DDL_OK;
 }
 
+// Adds the tables of the step-fused path to the plan's entry for the current device.
+template <typename T>
+bool upload(T** d, const std::vector<T>& h) {
+    if (hipMalloc(reinterpret_cast<void**>(d), h.size() * sizeof(T)) != hipSuccess) return false;
+    return hipMemcpy(*d, h.data(), h.size() * sizeof(T), hipMemcpyHostToDevice) == hipSuccess;
+}
+
+ddl_status_t fused_tables(const ddl_plan* plan, DeviceTables* out) {
+    DeviceTables base;
+    ddl_status_t st = device_tables(plan, &base);
+    if (st != DDL_OK) return st;
+    std::lock_guard<std::mutex> lock(plan->mu);
+    for (DeviceTables& t : plan->tables) {
+        if (t.device != base.device) continue;
+        if (t.fused_seq == nullptr) {
+            std::vector<uint32_t> seq, ctl;
+            int padded = 0;
+            t.fused_levels = ddl::build_fused_order(*plan, &seq, &ctl, &padded);
+            t.fused_padded = padded;
+            const bool ok = upload(&t.fused_seq, seq) && upload(&t.fused_ctl, ctl) &&
+                            upload(&t.fused_n, plan->own_n) && upload(&t.fused_off, plan->own_off) &&
+                            hipMalloc(reinterpret_cast<void**>(&t.fused_ptrs),
+                                      seq.size() * sizeof(uint64_t)) == hipSuccess;
+            if (!ok) {
+                uint32_t** p32[] = {&t.fused_seq, &t.fused_ctl};
+                uint64_t** p64[] = {&t.fused_n, &t.fused_off, &t.fused_ptrs};
+                for (uint32_t** p : p32) {
+                    if (*p) (void)hipFree(*p);
+                    *p = nullptr;
+                }
+                for (uint64_t** p : p64) {
+                    if (*p) (void)hipFree(*p);
+                    *p = nullptr;
+                }
+                return DDL_ERR_NOMEM;
+            }
+        }
+        *out = t;
+        return DDL_OK;
+    }
+    return DDL_ERR_HIP;
+}
+
 ddl_status_t check_call(void** bufs, int P, const ddl_plan* plan, size_t count, ddl_dtype_t dtype) {
     if (plan == nullptr || bufs == nullptr || P < 1) return DDL_ERR_ARG;
     if (ddl::dtype_size(dtype) == 0) return DDL_ERR_DTYPE;
@@ -160,6 +203,11 @@ void ddl_plan_free(ddl_plan_t* plan) {
         if (t.ops) (void)hipFree(t.ops);
         if (t.rops) (void)hipFree(t.rops);
         if (t.ptrs) (void)hipFree(t.ptrs);
+        if (t.fused_seq) (void)hipFree(t.fused_seq);
+        if (t.fused_ctl) (void)hipFree(t.fused_ctl);
+        if (t.fused_n) (void)hipFree(t.fused_n);
+        if (t.fused_off) (void)hipFree(t.fused_off);
+        if (t.fused_ptrs) (void)hipFree(t.fused_ptrs);
     }
     delete plan;
 }
@@ -187,6 +235,38 @@ ddl_status_t ddl_allgather_sim(void** bufs, int P, const ddl_plan_t* plan, size_
     const int split = plan ? plan->first_gather : 0;
     const int steps = plan ? static_cast<int>(plan->steps.size()) : 0;
     return run_steps(bufs, P, plan, count, dtype, stream, split, steps, nullptr);
+}
+
+ddl_status_t ddl_allreduce_fused_sim(void** bufs, int P, const ddl_plan_t* plan, size_t count,
+                                     ddl_dtype_t dtype, void* stream_v) {
+    ddl_status_t st = check_call(bufs, P, plan, count, dtype);
+    if (st != DDL_OK) return st;
+    int levels = 0;
+    for (int d : plan->dims) levels += d > 1;
+    if (P > DDL_FUSED_MAX_LEARNERS || levels > DDL_FUSED_MAX_LEVELS) return DDL_ERR_UNSUPPORTED;
+    if (count == 0 || levels == 0) return DDL_OK;
+    hipStream_t stream = static_cast<hipStream_t>(stream_v);
+    DeviceTables t;
+    st = fused_tables(plan, &t);
+    if (st != DDL_OK) return st;
+    PtrTable table;
+    void* const* d_ptrs = nullptr;
+    if (P <= ddl::kKernargLearners) {
+        std::memset(&table, 0, sizeof(table));
+        std::memcpy(table.p, bufs, size_t(P) * sizeof(void*));
+    } else {
+        if (hipMemcpyAsync(t.ptrs, bufs, size_t(P) * sizeof(void*), hipMemcpyHostToDevice, stream) !=
+            hipSuccess)
+            return DDL_ERR_HIP;
+        d_ptrs = t.ptrs;
+    }
+    if (ddl::launch_fused_resolve(*plan, t, t.fused_padded, t.fused_off, table, d_ptrs, stream) != hipSuccess)
+        return DDL_ERR_HIP;
+    uint64_t max_chunk = 0;
+    for (uint64_t n : plan->own_n) max_chunk = n > max_chunk ? n : max_chunk;
+    if (ddl::launch_fused(*plan, t, t.fused_padded, t.fused_levels, max_chunk, stream) != hipSuccess)
+        return DDL_ERR_HIP;
+    return DDL_OK;
 }
 
 ddl_status_t ddl_allreduce_sim_profile(void** bufs, int P, const ddl_plan_t* plan, size_t count,
@@ -257,6 +337,10 @@ int ddl_plan_num_learners(const ddl_plan_t* plan) { return plan ? plan->P : 0; }
 
 size_t ddl_plan_bytes_moved(const ddl_plan_t* plan) { return plan ? plan->bytes_total : 0; }
 
+size_t ddl_plan_fused_bytes(const ddl_plan_t* plan) {
+    return plan ? size_t(2) * plan->elem_size * plan->count * plan->P : 0;
+}
+
 size_t ddl_plan_step_bytes(const ddl_plan_t* plan, int step) {
     if (plan == nullptr || step < 0 || step >= static_cast<int>(plan->steps.size())) return 0;
     return plan->steps[step].bytes;
@@ -309,6 +393,7 @@ const char* ddl_status_string(ddl_status_t status) {
         case DDL_ERR_PLAN_MISMATCH: return "arguments differ from the plan's";
         case DDL_ERR_NOMEM: return "out of memory";
         case DDL_ERR_HIP: return "HIP runtime error";
+        case DDL_ERR_UNSUPPORTED: return "not supported by this entry point";
     }
     return "unknown status";
 }

@@ -25,4 +25,13 @@ hipError_t launch_resolve(const ddl_plan& plan, const Op* d_ops, ResolvedOp* d_r
 hipError_t launch_step(const ddl_plan& plan, const Step& step, const ResolvedOp* d_rops,
                        hipStream_t stream);
 
+// Step-fused allreduce.  launch_fused_resolve binds the summation-order table to the
+// caller's buffers: d_ptrs_out[c * padded + i] = address of finest chunk c in learner
+// seq[c][i].  launch_fused runs the single pass over all chunks.
+hipError_t launch_fused_resolve(const ddl_plan& plan, const DeviceTables& t, int padded,
+                                const uint64_t* d_own_off, const PtrTable& table,
+                                void* const* d_ptrs, hipStream_t stream);
+hipError_t launch_fused(const ddl_plan& plan, const DeviceTables& t, int padded, int levels,
+                        uint64_t max_chunk, hipStream_t stream);
+
 }  // namespace ddl

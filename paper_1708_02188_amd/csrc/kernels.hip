@@ -54,12 +54,14 @@ template <> struct Elem<float> {
     typedef float V __attribute__((ext_vector_type(4)));
     static __device__ __forceinline__ V add(V a, V b) { return a + b; }
     static __device__ __forceinline__ S add1(S a, S b) { return a + b; }
+    template <typename X> static __device__ __forceinline__ X sum(X a, X b) { return a + b; }
 };
 template <> struct Elem<double> {
     typedef double S;
     typedef double V __attribute__((ext_vector_type(2)));
     static __device__ __forceinline__ V add(V a, V b) { return a + b; }
     static __device__ __forceinline__ S add1(S a, S b) { return a + b; }
+    template <typename X> static __device__ __forceinline__ X sum(X a, X b) { return a + b; }
 };
 // 32-bit integers are summed as unsigned: wrap-around, the same bits as two's complement
 template <> struct Elem<unsigned> {
@@ -67,12 +69,14 @@ template <> struct Elem<unsigned> {
     typedef unsigned V __attribute__((ext_vector_type(4)));
     static __device__ __forceinline__ V add(V a, V b) { return a + b; }
     static __device__ __forceinline__ S add1(S a, S b) { return a + b; }
+    template <typename X> static __device__ __forceinline__ X sum(X a, X b) { return a + b; }
 };
 template <> struct Elem<_Float16> {
     typedef _Float16 S;
     typedef _Float16 V __attribute__((ext_vector_type(8)));
     static __device__ __forceinline__ V add(V a, V b) { return a + b; }
     static __device__ __forceinline__ S add1(S a, S b) { return a + b; }
+    template <typename X> static __device__ __forceinline__ X sum(X a, X b) { return a + b; }
 };
 // bfloat16 travels as its 16 raw bits; widened to binary32 (exact), added there, and
 // rounded back to the nearest bfloat16, ties to even.
@@ -94,7 +98,16 @@ template <> struct Elem<bf16_bits> {
         for (int i = 0; i < 8; ++i) r[i] = add1(a[i], b[i]);
         return r;
     }
+    template <typename X> static __device__ __forceinline__ X sum(X a, X b);
 };
+template <> __device__ __forceinline__ unsigned short Elem<bf16_bits>::sum<unsigned short>(unsigned short a,
+                                                                                          unsigned short b) {
+    return add1(a, b);
+}
+template <> __device__ __forceinline__ Elem<bf16_bits>::V Elem<bf16_bits>::sum<Elem<bf16_bits>::V>(
+    Elem<bf16_bits>::V a, Elem<bf16_bits>::V b) {
+    return add(a, b);
+}
 
 // Pointers are tagged as global memory so the loads and stores are global_* rather than
 // flat_* instructions (no aperture check, no LDS counter involvement).
@@ -218,6 +231,110 @@ hipError_t launch_typed(const ddl_plan& plan, const Step& step, const ResolvedOp
     return hipGetLastError();
 }
 
+// ---------------------------------------------------------------------------------------
+// Step-fused allreduce
+// ---------------------------------------------------------------------------------------
+// Tables are read through the constant address space so that every access is a scalar
+// load even after the kernel has started storing to the learners' buffers.
+#define DDL_CONST __attribute__((address_space(4)))
+
+__global__ __launch_bounds__(256) void fused_resolve(const PtrTable table, void* const* __restrict__ d_ptrs,
+                                                     const uint32_t* __restrict__ seq,
+                                                     const uint64_t* __restrict__ own_off,
+                                                     uint64_t* __restrict__ out, unsigned P, unsigned padded,
+                                                     unsigned elem_size) {
+    const unsigned i = blockIdx.x * 256u + threadIdx.x;
+    if (i >= P * padded) return;
+    const unsigned c = i / padded;
+    const unsigned r = seq[i];
+    const uint64_t base = reinterpret_cast<uint64_t>(d_ptrs ? d_ptrs[r] : table.p[r]);
+    out[i] = base + own_off[c] * elem_size;
+}
+
+// One item enters the nest of ring folds: level 0 takes the learner's value; a level that
+// this item completes hands its sum on to the next level (Sec. 4.3: the box is reduced
+// one dimension after the other, each ring adding its partial results in ring order).
+// `word` is uniform across the wave, so every branch here is a scalar branch.
+template <typename T, typename X>
+__device__ __forceinline__ void fused_feed(X (&acc)[DDL_FUSED_MAX_LEVELS], X v, uint32_t word, int levels) {
+    if (word & 1u) acc[0] = v;
+    else acc[0] = Elem<T>::template sum<X>(acc[0], v);
+    if (!(word & 0x100u)) return;  // the ring of level 0 is not complete yet
+    v = acc[0];
+#pragma unroll
+    for (int t = 1; t < DDL_FUSED_MAX_LEVELS; ++t) {
+        if (t >= levels) return;
+        if ((word >> t) & 1u) acc[t] = v;
+        else acc[t] = Elem<T>::template sum<X>(acc[t], v);
+        if (!((word >> (8 + t)) & 1u)) return;
+        v = acc[t];
+    }
+}
+
+// All P learners' values at one place (a 16-byte vector X = V, or one element X = S):
+// fold them in schedule order, store the result to every learner.
+template <typename T, typename X>
+__device__ __forceinline__ void fused_fold_store(const DDL_CONST uint64_t* row, const DDL_CONST uint32_t* ctl,
+                                                 int P, int padded, int levels, uint64_t byte_off) {
+    X acc[DDL_FUSED_MAX_LEVELS];
+    for (int i0 = 0; i0 < padded; i0 += kFusedBatch) {
+        X x[kFusedBatch];
+#pragma unroll
+        for (int j = 0; j < kFusedBatch; ++j)
+            x[j] = stream_load((const DDL_GLOBAL X*)(row[i0 + j] + byte_off));
+#pragma unroll
+        for (int j = 0; j < kFusedBatch; ++j) {
+            const uint32_t word = ctl[i0 + j];
+            if (word & kFusedValid) fused_feed<T, X>(acc, x[j], word, levels);
+        }
+    }
+    const X result = acc[levels - 1];
+    for (int i0 = 0; i0 < padded; i0 += kFusedBatch) {
+#pragma unroll
+        for (int j = 0; j < kFusedBatch; ++j)
+            if (i0 + j < P) stream_store((DDL_GLOBAL X*)(row[i0 + j] + byte_off), result);
+    }
+}
+
+template <typename T>
+__global__ __launch_bounds__(64) void fused_allreduce_kernel(const uint64_t* ptrs_, const uint32_t* ctl_,
+                                                             const uint64_t* chunk_n_, int P, int padded,
+                                                             int levels, unsigned tile_stride) {
+    typedef typename Elem<T>::V V;
+    typedef typename Elem<T>::S S;
+    constexpr int64_t VL = 16 / sizeof(S);
+    const DDL_CONST uint64_t* row = (const DDL_CONST uint64_t*)ptrs_ + size_t(blockIdx.y) * padded;
+    const DDL_CONST uint32_t* ctl = (const DDL_CONST uint32_t*)ctl_;
+    const int64_t n = int64_t(((const DDL_CONST uint64_t*)chunk_n_)[blockIdx.y]);
+    const int64_t nv = n / VL;
+    const int64_t shift = int64_t((row[0] % kRowBytes) / 16);
+    const int64_t tid = threadIdx.x;
+
+    for (int64_t first = int64_t(blockIdx.x) * 64 - shift; first <= nv; first += int64_t(tile_stride) * 64) {
+        const int64_t v = first + tid;
+        if (v >= 0 && v < nv) {
+            fused_fold_store<T, V>(row, ctl, P, padded, levels, uint64_t(v) * 16);
+        } else if (v == nv) {
+            // the buffer's last, short vector: element by element
+            for (int64_t e = nv * VL; e < n; ++e)
+                fused_fold_store<T, S>(row, ctl, P, padded, levels, uint64_t(e) * sizeof(S));
+        }
+    }
+}
+
+template <typename T>
+hipError_t launch_fused_typed(const ddl_plan& plan, const DeviceTables& t, int padded, int levels,
+                              uint64_t max_chunk, hipStream_t stream) {
+    constexpr uint64_t VL = 16 / sizeof(typename Elem<T>::S);
+    uint64_t tiles = (max_chunk / VL + 1 + (kRowVecs - 1) + 63) / 64;
+    const uint64_t max_x = ((uint64_t(1) << 32) / 64 - 1) / uint64_t(plan.P);
+    if (tiles > max_x) tiles = max_x;
+    const dim3 grid(static_cast<unsigned>(tiles), static_cast<unsigned>(plan.P), 1);
+    hipLaunchKernelGGL((fused_allreduce_kernel<T>), grid, dim3(64), 0, stream, t.fused_ptrs, t.fused_ctl,
+                       t.fused_n, plan.P, padded, levels, grid.x);
+    return hipGetLastError();
+}
+
 }  // namespace
 
 hipError_t launch_resolve(const ddl_plan& plan, const Op* d_ops, ResolvedOp* d_rops,
@@ -238,6 +355,28 @@ hipError_t launch_step(const ddl_plan& plan, const Step& step, const ResolvedOp*
         case DDL_I32: return launch_typed<unsigned>(plan, step, d_rops, stream);
         case DDL_F16: return launch_typed<_Float16>(plan, step, d_rops, stream);
         case DDL_BF16: return launch_typed<bf16_bits>(plan, step, d_rops, stream);
+    }
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_fused_resolve(const ddl_plan& plan, const DeviceTables& t, int padded,
+                                const uint64_t* d_own_off, const PtrTable& table,
+                                void* const* d_ptrs, hipStream_t stream) {
+    const unsigned total = unsigned(plan.P) * unsigned(padded);
+    hipLaunchKernelGGL(fused_resolve, dim3((total + 255) / 256), dim3(256), 0, stream, table, d_ptrs,
+                       t.fused_seq, d_own_off, t.fused_ptrs, unsigned(plan.P), unsigned(padded),
+                       unsigned(plan.elem_size));
+    return hipGetLastError();
+}
+
+hipError_t launch_fused(const ddl_plan& plan, const DeviceTables& t, int padded, int levels,
+                        uint64_t max_chunk, hipStream_t stream) {
+    switch (plan.dtype) {
+        case DDL_F32: return launch_fused_typed<float>(plan, t, padded, levels, max_chunk, stream);
+        case DDL_F64: return launch_fused_typed<double>(plan, t, padded, levels, max_chunk, stream);
+        case DDL_I32: return launch_fused_typed<unsigned>(plan, t, padded, levels, max_chunk, stream);
+        case DDL_F16: return launch_fused_typed<_Float16>(plan, t, padded, levels, max_chunk, stream);
+        case DDL_BF16: return launch_fused_typed<bf16_bits>(plan, t, padded, levels, max_chunk, stream);
     }
     return hipErrorInvalidValue;
 }

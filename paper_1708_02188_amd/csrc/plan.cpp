@@ -93,6 +93,51 @@ void build_schedule(ddl_plan* plan) {
         for (int phase = 0; phase + 1 < plan->dims[t]; ++phase) emit(DDL_STEP_GATHER, t, phase);
 }
 
+int build_fused_order(const ddl_plan& plan, std::vector<uint32_t>* seq, std::vector<uint32_t>* ctl,
+                      int* padded) {
+    // Rings of size 1 add nothing; the others are the levels, dimension 1 innermost.
+    std::vector<int> size, stride;
+    int s = 1;
+    for (int d : plan.dims) {
+        if (d > 1) {
+            size.push_back(d);
+            stride.push_back(s);
+        }
+        s *= d;
+    }
+    const int levels = static_cast<int>(size.size());
+    const int P = plan.P;
+    const int pad = (P + kFusedBatch - 1) / kFusedBatch * kFusedBatch;
+    *padded = pad;
+    seq->assign(size_t(P) * pad, 0);
+    ctl->assign(pad, 0);
+    std::vector<int> digit(levels, 0);
+    for (int i = 0; i < P; ++i) {
+        // item i = mixed-radix digits (i_1 fastest): position k_t + 1 + i_t on the ring of level t
+        uint32_t word = kFusedValid;
+        for (int t = 0; t < levels; ++t) {
+            if (digit[t] == 0) word |= 1u << t;
+            if (digit[t] == size[t] - 1) word |= 1u << (8 + t);
+        }
+        (*ctl)[i] = word;
+        for (int c = 0; c < P; ++c) {
+            int rank = 0;
+            for (int t = 0; t < levels; ++t) {
+                const int k = (c / stride[t]) % size[t];
+                rank += ((k + 1 + digit[t]) % size[t]) * stride[t];
+            }
+            (*seq)[size_t(c) * pad + i] = static_cast<uint32_t>(rank);
+        }
+        for (int t = 0; t < levels; ++t) {
+            if (++digit[t] < size[t]) break;
+            digit[t] = 0;
+        }
+    }
+    for (int c = 0; c < P; ++c)
+        for (int i = P; i < pad; ++i) (*seq)[size_t(c) * pad + i] = (*seq)[size_t(c) * pad];
+    return levels;
+}
+
 double model_time(const int* dims, int m, double bytes, const double* bw, const double* lat) {
     double level_bytes = bytes;
     double total = 0.0;

@@ -37,11 +37,26 @@ struct Step {
     uint64_t bytes;  // memory traffic of the phase
 };
 
+// Tables of the step-fused allreduce.  Finest chunk c (owned by learner c) is summed over
+// the learners in the order seq[c][0..P-1]; ctl[i] says which ring levels item i opens
+// (bits 0-7) and closes (bits 8-15); bit 31 marks a real item (rows are padded to a
+// multiple of kFusedBatch).
+constexpr int kFusedBatch = 8;
+constexpr uint32_t kFusedValid = 0x80000000u;
+
 struct DeviceTables {
     int device = -1;
     Op* ops = nullptr;           // num_steps * P operations, step-major
     ResolvedOp* rops = nullptr;  // the same operations bound to the buffers of the latest call
     void** ptrs = nullptr;       // staging for the learner pointers when P exceeds the kernarg table
+    // step-fused path, created at its first use
+    uint32_t* fused_seq = nullptr;    // P * padded learner ranks
+    uint32_t* fused_ctl = nullptr;    // padded control words
+    uint64_t* fused_n = nullptr;      // elements of each finest chunk
+    uint64_t* fused_off = nullptr;    // element offset of each finest chunk
+    int fused_levels = 0;             // box dimensions of size > 1
+    int fused_padded = 0;             // row length of fused_seq / fused_ptrs
+    uint64_t* fused_ptrs = nullptr;   // P * padded absolute addresses, bound per call
 };
 
 }  // namespace ddl
@@ -74,6 +89,11 @@ void split_range(uint64_t lo, uint64_t hi, uint64_t d, uint64_t k, uint64_t G,
 void build_schedule(ddl_plan* plan);
 
 ddl_status_t validate_dims(const int* dims, int m, int P);
+
+// Summation order of the step-fused allreduce; returns the number of box dimensions of
+// size > 1 ("levels") and the padded row length.  seq: P * padded, ctl: padded.
+int build_fused_order(const ddl_plan& plan, std::vector<uint32_t>* seq, std::vector<uint32_t>* ctl,
+                      int* padded);
 
 // Estimated cluster time of reduction + distribution for a box (Sec. 4.3 ring estimate per
 // dimension, on the bytes left at that level).

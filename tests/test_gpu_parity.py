@@ -250,6 +250,91 @@ def test_more_learners_than_the_kernarg_table_holds(dev):
 
 
 # ---------------------------------------------------------------------------------------
+# step-fused allreduce: same final bits as the phase-by-phase schedule
+# ---------------------------------------------------------------------------------------
+FUSED_CASES = [([1], 100), ([2], 1), ([4], 37), ([4], 65536 + 5), ([3], 100003), ([2, 3], 50001), ([4, 4], 300007),
+               ([3, 1, 2], 70001), ([4, 2, 2], 262144 + 13), ([2, 2, 2, 2], 99999), ([16], 150001),
+               ([4, 16], 200003), ([4, 8, 8], 1000), ([4, 8, 8], 300001), ([7, 3], 123457), ([5], 3), ([2, 2], 0),
+               ([1, 4, 1, 2, 1], 4099)]
+
+
+@pytest.mark.parametrize("dims,count", FUSED_CASES)
+def test_fused_allreduce_matches_fold_fp32(dev, dims, count):
+    P = prod(dims)
+    say(f"fused allreduce f32 dims={dims} count={count}")
+    rng = np.random.default_rng(4000 + count + P)
+    V = wide_inputs(rng, P, count, D.DDL_F32)
+    bufs = upload(V, dev)
+    plan = D.ddl_ring_plan(dims, P, count)
+    D.ddl_allreduce_fused_sim(bufs, P, plan, count, D.DDL_F32, torch.cuda.current_stream())
+    got = download(bufs)
+    want = O.allreduce_fold(V, dims)
+    for j in range(P):
+        assert_bitwise(got[j], want, f"fused dims={dims} count={count} learner={j}")
+    # and therefore the same as executing the phases
+    bufs2 = upload(V, dev)
+    D.ddl_allreduce_sim(bufs2, P, plan, count)
+    for j, g in enumerate(download(bufs2)):
+        assert_bitwise(g, got[j], f"fused vs phases learner={j}")
+
+
+@pytest.mark.parametrize("dtype", [D.DDL_F64, D.DDL_I32, D.DDL_F16, D.DDL_BF16])
+@pytest.mark.parametrize("dims,count", [([4], 10001), ([2, 3], 65537), ([4, 4], 131072 + 3), ([3], 1), ([4, 2, 2], 7)])
+def test_fused_allreduce_other_dtypes(dev, dtype, dims, count):
+    P = prod(dims)
+    say(f"fused allreduce dtype={dtype} dims={dims} count={count}")
+    rng = np.random.default_rng(99 + count)
+    V = wide_inputs(rng, P, count, dtype)
+    bufs = upload(V, dev)
+    plan = D.ddl_ring_plan(dims, P, count, dtype)
+    D.ddl_allreduce_fused_sim(bufs, P, plan, count, dtype)
+    got = download(bufs, NP_OF[dtype])
+    with np.errstate(over="ignore"):
+        want = O.allreduce_fold(V, dims, add=O.bf16_add if dtype == D.DDL_BF16 else None)
+    for j in range(P):
+        assert_bitwise(got[j], want, f"fused dtype={dtype} dims={dims} learner={j}")
+
+
+def test_fused_allreduce_many_learners_and_limits(dev):
+    dims, count, P = [8, 8, 8], 70001, 512
+    V = [I.fill_host(count, 5, j, "uniform") for j in range(P)]
+    bufs = upload(V, dev)
+    plan = D.ddl_ring_plan(dims, P, count)
+    D.ddl_allreduce_fused_sim(bufs, P, plan, count)
+    want = O.allreduce_fold(V, dims)
+    for j, g in enumerate(download(bufs)):
+        assert_bitwise(g, want, f"fused P=512 learner={j}")
+    # five rings of size 2: more levels than the fused kernel nests
+    plan5 = D.ddl_ring_plan([2] * 5, 32, 64)
+    small = [torch.zeros(64, dtype=torch.float32, device=dev) for _ in range(32)]
+    with pytest.raises(D.DdlError) as e:
+        D.ddl_allreduce_fused_sim(small, 32, plan5, 64)
+    assert e.value.status == D.DDL_ERR_UNSUPPORTED
+
+
+@pytest.mark.parametrize("idx", [1, 3])
+def test_fused_allreduce_full_size(dev, idx):
+    cfg = I.CONFIGS[idx]
+    P, dims, count, dist, seed = cfg["P"], cfg["dims"], cfg["count"], cfg["dist"], cfg["seed"]
+    say(f"fused config {cfg['name']}")
+    bufs = [torch.empty(count, dtype=torch.float32, device=dev) for _ in range(P)]
+    for j, b in enumerate(bufs):
+        I.fill_device(b, seed, j, dist)
+    plan = D.ddl_ring_plan(dims, P, count)
+    D.ddl_allreduce_fused_sim(bufs, P, plan, count, D.DDL_F32, torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    for j in range(1, P):
+        assert torch.equal(bufs[0].view(torch.int32), bufs[j].view(torch.int32)), f"learner {j} differs"
+    got = bufs[0].cpu().numpy()
+    del bufs
+    torch.cuda.empty_cache()
+    for a, b in sample_ranges(plan, P, count):
+        want = O.allreduce_fold_range(lambda r, lo, hi: I.fill_host(hi - lo, seed, r, dist, first=lo),
+                                      dims, count, a, b, np.float32)
+        assert_bitwise(got[a:b], want, f"fused {cfg['name']} [{a},{b})")
+
+
+# ---------------------------------------------------------------------------------------
 # the benchmark configurations at full size, device-generated inputs
 # ---------------------------------------------------------------------------------------
 def sample_ranges(plan, P, count, width=2048, extra=12):

@@ -115,7 +115,7 @@ def test_plan_argument_errors():
     assert status_of(D.ddl_ring_plan, [4], 4, 10, 99) == D.DDL_ERR_DTYPE
     assert status_of(D.ddl_ring_plan, None, 4, 10) == D.DDL_ERR_ARG
     assert status_of(D.ddl_ring_plan, [65536], 65536, 10) == D.DDL_ERR_ARG
-    for code in range(-7, 1):
+    for code in range(-8, 1):
         assert D.ddl_status_string(code) and D.ddl_status_string(code) != "unknown status"
     assert D.ddl_status_string(-99) == "unknown status"
     assert D.ddl_plan_num_steps(None) == -1 and D.ddl_plan_bytes_moved(None) == 0
@@ -125,7 +125,7 @@ def test_plan_argument_errors():
 
 @pytest.mark.parametrize("entry", [D.ddl_allreduce_sim, D.ddl_reduce_scatter_sim,
                                    D.ddl_allgather_sim, D.ddl_allreduce_sim_profile,
-                                   D.ddl_allreduce_sim_timed])
+                                   D.ddl_allreduce_sim_timed, D.ddl_allreduce_fused_sim])
 def test_call_argument_errors(entry):
     count = 64
     plan = D.ddl_ring_plan([2, 2], 4, count)
@@ -141,6 +141,19 @@ def test_call_argument_errors(entry):
     assert status_of(entry, [good[0], good[1], good[1], good[3]], 4, plan, count) == D.DDL_ERR_ARG
     # overlapping, not identical: buffers of 256 bytes only 128 bytes apart
     assert status_of(entry, [good[0], good[0] + 128, good[2], good[3]], 4, plan, count) == D.DDL_ERR_ARG
+
+
+def test_fused_limits_and_bytes():
+    plan = D.ddl_ring_plan([4, 8, 8], 256, 25557032)
+    assert D.ddl_plan_fused_bytes(plan) == 8 * 25557032 * 256
+    assert D.ddl_plan_fused_bytes(None) == 0
+    # rejected on the host, before any device work: too many learners / too many levels
+    big = D.ddl_ring_plan([2048], 2048, 64)
+    ptrs = [0x100000 + 0x1000 * j for j in range(2048)]
+    assert status_of(D.ddl_allreduce_fused_sim, ptrs, 2048, big, 64) == D.DDL_ERR_UNSUPPORTED
+    deep = D.ddl_ring_plan([2] * 5, 32, 64)
+    assert status_of(D.ddl_allreduce_fused_sim, ptrs[:32], 32, deep, 64) == D.DDL_ERR_UNSUPPORTED
+    D.ddl_allreduce_fused_sim([0x100000], 1, D.ddl_ring_plan([1, 1], 1, 100), 100)  # one learner: nothing to do
 
 
 def test_trivial_calls_need_no_device():
