@@ -147,8 +147,10 @@ ddl_status_t ddl_allreduce_sim_timed(void** bufs, int P, const ddl_plan_t* plan,
  * that reads every learner's element once, folds the ring orders of all dimensions in
  * registers and writes the result to every learner, instead of executing the phases one
  * by one.  The partial sums the phases would have left in the buffers on the way are never
- * materialised.  Memory traffic is 2 * sizeof(element) * count * P bytes
- * (ddl_plan_fused_bytes) instead of ddl_plan_bytes_moved.
+ * materialised.  Memory traffic is 2 * sizeof(element) * count * P bytes instead of
+ * ddl_plan_bytes_moved; from 32 learners on the work is split into a reducing pass (result
+ * to the chunk's owner) and a distributing pass, which adds one write and one read of the
+ * result (ddl_plan_fused_bytes gives the exact figure).
  * Same arguments, rules and errors as ddl_allreduce_sim; additionally
  * DDL_ERR_UNSUPPORTED if P > DDL_FUSED_MAX_LEARNERS or the box has more than
  * DDL_FUSED_MAX_LEVELS dimensions of size > 1 (use ddl_allreduce_sim then).
@@ -173,7 +175,7 @@ int ddl_plan_num_learners(const ddl_plan_t* plan);
 size_t ddl_plan_bytes_moved(const ddl_plan_t* plan);
 
 /* Bytes ddl_allreduce_fused_sim moves: every element of every learner read once and
- * written once. */
+ * written once, plus one write and read of the result when it runs as two passes. */
 size_t ddl_plan_fused_bytes(const ddl_plan_t* plan);
 
 /* ddl_plan_bytes_moved for one step; 0 for a bad index. */

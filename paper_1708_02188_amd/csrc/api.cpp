@@ -264,8 +264,17 @@ ddl_status_t ddl_allreduce_fused_sim(void** bufs, int P, const ddl_plan_t* plan,
         return DDL_ERR_HIP;
     uint64_t max_chunk = 0;
     for (uint64_t n : plan->own_n) max_chunk = n > max_chunk ? n : max_chunk;
-    if (ddl::launch_fused(*plan, t, t.fused_padded, t.fused_levels, max_chunk, stream) != hipSuccess)
+    // Measured on MI355X: from about 32 learners on, two passes (all reads of the reduction
+    // first, then all writes of the distribution) sustain more bandwidth than one pass that
+    // mixes P read and P write streams, at the price of writing and re-reading the result
+    // once (1/P more traffic); below that the second launch costs more than it gains.
+    if (P >= 32) {
+        if (ddl::launch_fused(*plan, t, t.fused_padded, t.fused_levels, max_chunk, 1, stream) != hipSuccess ||
+            ddl::launch_fused(*plan, t, t.fused_padded, t.fused_levels, max_chunk, 2, stream) != hipSuccess)
+            return DDL_ERR_HIP;
+    } else if (ddl::launch_fused(*plan, t, t.fused_padded, t.fused_levels, max_chunk, 0, stream) != hipSuccess) {
         return DDL_ERR_HIP;
+    }
     return DDL_OK;
 }
 
@@ -338,7 +347,10 @@ int ddl_plan_num_learners(const ddl_plan_t* plan) { return plan ? plan->P : 0; }
 size_t ddl_plan_bytes_moved(const ddl_plan_t* plan) { return plan ? plan->bytes_total : 0; }
 
 size_t ddl_plan_fused_bytes(const ddl_plan_t* plan) {
-    return plan ? size_t(2) * plan->elem_size * plan->count * plan->P : 0;
+    if (plan == nullptr) return 0;
+    // one pass: P reads + P writes per element; two passes: one more write and read
+    const size_t per_elem = plan->P >= 32 ? size_t(2) * plan->P + 2 : size_t(2) * plan->P;
+    return per_elem * plan->elem_size * plan->count;
 }
 
 size_t ddl_plan_step_bytes(const ddl_plan_t* plan, int step) {

@@ -31,7 +31,9 @@ hipError_t launch_step(const ddl_plan& plan, const Step& step, const ResolvedOp*
 hipError_t launch_fused_resolve(const ddl_plan& plan, const DeviceTables& t, int padded,
                                 const uint64_t* d_own_off, const PtrTable& table,
                                 void* const* d_ptrs, hipStream_t stream);
+// mode: 0 = fold and store to all learners, 1 = fold and store to the chunk's owner,
+// 2 = copy the owner's chunk to all other learners.
 hipError_t launch_fused(const ddl_plan& plan, const DeviceTables& t, int padded, int levels,
-                        uint64_t max_chunk, hipStream_t stream);
+                        uint64_t max_chunk, int mode, hipStream_t stream);
 
 }  // namespace ddl

@@ -271,35 +271,51 @@ __device__ __forceinline__ void fused_feed(X (&acc)[DDL_FUSED_MAX_LEVELS], X v, 
     }
 }
 
-// All P learners' values at one place (a 16-byte vector X = V, or one element X = S):
-// fold them in schedule order, store the result to every learner.
-template <typename T, typename X>
-__device__ __forceinline__ void fused_fold_store(const DDL_CONST uint64_t* row, const DDL_CONST uint32_t* ctl,
-                                                 int P, int padded, int levels, uint64_t byte_off) {
-    X acc[DDL_FUSED_MAX_LEVELS];
-    for (int i0 = 0; i0 < padded; i0 += kFusedBatch) {
-        X x[kFusedBatch];
+// What one pass of the fused kernel does at every place of a finest chunk.
+enum { FUSED_ALL = 0,      // fold all learners, store the result to all of them
+       FUSED_REDUCE = 1,   // fold all learners, store the result to the chunk's owner only
+       FUSED_GATHER = 2 }; // copy the owner's value to every other learner
+
+// All P learners' values at one place (a 16-byte vector X = V, or one element X = S).
+// The chunk's owner is the last learner of the summation order (the partial sum travels
+// once round every ring and ends at the owner's position).
+template <typename T, typename X, int MODE>
+__device__ __forceinline__ void fused_place(const DDL_CONST uint64_t* row, const DDL_CONST uint32_t* ctl,
+                                            int P, int padded, int levels, uint64_t byte_off) {
+    X result;
+    if (MODE == FUSED_GATHER) {
+        result = stream_load((const DDL_GLOBAL X*)(row[P - 1] + byte_off));
+    } else {
+        X acc[DDL_FUSED_MAX_LEVELS];
+        for (int i0 = 0; i0 < padded; i0 += kFusedBatch) {
+            X x[kFusedBatch];
 #pragma unroll
-        for (int j = 0; j < kFusedBatch; ++j)
-            x[j] = stream_load((const DDL_GLOBAL X*)(row[i0 + j] + byte_off));
+            for (int j = 0; j < kFusedBatch; ++j)
+                x[j] = stream_load((const DDL_GLOBAL X*)(row[i0 + j] + byte_off));
 #pragma unroll
-        for (int j = 0; j < kFusedBatch; ++j) {
-            const uint32_t word = ctl[i0 + j];
-            if (word & kFusedValid) fused_feed<T, X>(acc, x[j], word, levels);
+            for (int j = 0; j < kFusedBatch; ++j) {
+                const uint32_t word = ctl[i0 + j];
+                if (word & kFusedValid) fused_feed<T, X>(acc, x[j], word, levels);
+            }
         }
+        result = acc[levels - 1];
     }
-    const X result = acc[levels - 1];
-    for (int i0 = 0; i0 < padded; i0 += kFusedBatch) {
+    if (MODE == FUSED_REDUCE) {
+        stream_store((DDL_GLOBAL X*)(row[P - 1] + byte_off), result);
+        return;
+    }
+    const int stores = MODE == FUSED_GATHER ? P - 1 : P;
+    for (int i0 = 0; i0 < stores; i0 += kFusedBatch) {
 #pragma unroll
         for (int j = 0; j < kFusedBatch; ++j)
-            if (i0 + j < P) stream_store((DDL_GLOBAL X*)(row[i0 + j] + byte_off), result);
+            if (i0 + j < stores) stream_store((DDL_GLOBAL X*)(row[i0 + j] + byte_off), result);
     }
 }
 
-template <typename T>
-__global__ __launch_bounds__(64) void fused_allreduce_kernel(const uint64_t* ptrs_, const uint32_t* ctl_,
-                                                             const uint64_t* chunk_n_, int P, int padded,
-                                                             int levels, unsigned tile_stride) {
+template <typename T, int MODE>
+__global__ __launch_bounds__(64) void fused_kernel(const uint64_t* ptrs_, const uint32_t* ctl_,
+                                                   const uint64_t* chunk_n_, int P, int padded,
+                                                   int levels, unsigned tile_stride) {
     typedef typename Elem<T>::V V;
     typedef typename Elem<T>::S S;
     constexpr int64_t VL = 16 / sizeof(S);
@@ -307,31 +323,38 @@ __global__ __launch_bounds__(64) void fused_allreduce_kernel(const uint64_t* ptr
     const DDL_CONST uint32_t* ctl = (const DDL_CONST uint32_t*)ctl_;
     const int64_t n = int64_t(((const DDL_CONST uint64_t*)chunk_n_)[blockIdx.y]);
     const int64_t nv = n / VL;
-    const int64_t shift = int64_t((row[0] % kRowBytes) / 16);
+    const int64_t shift = int64_t((row[P - 1] % kRowBytes) / 16);
     const int64_t tid = threadIdx.x;
 
     for (int64_t first = int64_t(blockIdx.x) * 64 - shift; first <= nv; first += int64_t(tile_stride) * 64) {
         const int64_t v = first + tid;
         if (v >= 0 && v < nv) {
-            fused_fold_store<T, V>(row, ctl, P, padded, levels, uint64_t(v) * 16);
+            fused_place<T, V, MODE>(row, ctl, P, padded, levels, uint64_t(v) * 16);
         } else if (v == nv) {
             // the buffer's last, short vector: element by element
             for (int64_t e = nv * VL; e < n; ++e)
-                fused_fold_store<T, S>(row, ctl, P, padded, levels, uint64_t(e) * sizeof(S));
+                fused_place<T, S, MODE>(row, ctl, P, padded, levels, uint64_t(e) * sizeof(S));
         }
     }
 }
 
 template <typename T>
 hipError_t launch_fused_typed(const ddl_plan& plan, const DeviceTables& t, int padded, int levels,
-                              uint64_t max_chunk, hipStream_t stream) {
+                              uint64_t max_chunk, int mode, hipStream_t stream) {
     constexpr uint64_t VL = 16 / sizeof(typename Elem<T>::S);
     uint64_t tiles = (max_chunk / VL + 1 + (kRowVecs - 1) + 63) / 64;
     const uint64_t max_x = ((uint64_t(1) << 32) / 64 - 1) / uint64_t(plan.P);
     if (tiles > max_x) tiles = max_x;
     const dim3 grid(static_cast<unsigned>(tiles), static_cast<unsigned>(plan.P), 1);
-    hipLaunchKernelGGL((fused_allreduce_kernel<T>), grid, dim3(64), 0, stream, t.fused_ptrs, t.fused_ctl,
-                       t.fused_n, plan.P, padded, levels, grid.x);
+    if (mode == FUSED_ALL)
+        hipLaunchKernelGGL((fused_kernel<T, FUSED_ALL>), grid, dim3(64), 0, stream, t.fused_ptrs,
+                           t.fused_ctl, t.fused_n, plan.P, padded, levels, grid.x);
+    else if (mode == FUSED_REDUCE)
+        hipLaunchKernelGGL((fused_kernel<T, FUSED_REDUCE>), grid, dim3(64), 0, stream, t.fused_ptrs,
+                           t.fused_ctl, t.fused_n, plan.P, padded, levels, grid.x);
+    else
+        hipLaunchKernelGGL((fused_kernel<T, FUSED_GATHER>), grid, dim3(64), 0, stream, t.fused_ptrs,
+                           t.fused_ctl, t.fused_n, plan.P, padded, levels, grid.x);
     return hipGetLastError();
 }
 
@@ -370,13 +393,13 @@ hipError_t launch_fused_resolve(const ddl_plan& plan, const DeviceTables& t, int
 }
 
 hipError_t launch_fused(const ddl_plan& plan, const DeviceTables& t, int padded, int levels,
-                        uint64_t max_chunk, hipStream_t stream) {
+                        uint64_t max_chunk, int mode, hipStream_t stream) {
     switch (plan.dtype) {
-        case DDL_F32: return launch_fused_typed<float>(plan, t, padded, levels, max_chunk, stream);
-        case DDL_F64: return launch_fused_typed<double>(plan, t, padded, levels, max_chunk, stream);
-        case DDL_I32: return launch_fused_typed<unsigned>(plan, t, padded, levels, max_chunk, stream);
-        case DDL_F16: return launch_fused_typed<_Float16>(plan, t, padded, levels, max_chunk, stream);
-        case DDL_BF16: return launch_fused_typed<bf16_bits>(plan, t, padded, levels, max_chunk, stream);
+        case DDL_F32: return launch_fused_typed<float>(plan, t, padded, levels, max_chunk, mode, stream);
+        case DDL_F64: return launch_fused_typed<double>(plan, t, padded, levels, max_chunk, mode, stream);
+        case DDL_I32: return launch_fused_typed<unsigned>(plan, t, padded, levels, max_chunk, mode, stream);
+        case DDL_F16: return launch_fused_typed<_Float16>(plan, t, padded, levels, max_chunk, mode, stream);
+        case DDL_BF16: return launch_fused_typed<bf16_bits>(plan, t, padded, levels, max_chunk, mode, stream);
     }
     return hipErrorInvalidValue;
 }

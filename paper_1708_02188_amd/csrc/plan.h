@@ -41,7 +41,10 @@ struct Step {
 // the learners in the order seq[c][0..P-1]; ctl[i] says which ring levels item i opens
 // (bits 0-7) and closes (bits 8-15); bit 31 marks a real item (rows are padded to a
 // multiple of kFusedBatch).
-constexpr int kFusedBatch = 8;
+#ifndef DDL_FUSED_BATCH
+#define DDL_FUSED_BATCH 8
+#endif
+constexpr int kFusedBatch = DDL_FUSED_BATCH;
 constexpr uint32_t kFusedValid = 0x80000000u;
 
 struct DeviceTables {

@@ -209,6 +209,32 @@ def test_side_stream_profile_entry_and_repeat(dev):
         assert_bitwise(g, want1[j], f"timed learner={j}")
 
 
+def test_capture_into_a_hip_graph_and_replay(dev):
+    """The call is kernel launches only (P <= 256), so it can be stream-captured once the
+    plan's device tables exist; every replay must give the eager result."""
+    dims, count, P = [4, 2], 300007, 8
+    rng = np.random.default_rng(21)
+    V = wide_inputs(rng, P, count, D.DDL_F32)
+    want = O.allreduce_steps(V, dims)
+    plan = D.ddl_ring_plan(dims, P, count)
+    D.ddl_plan_prepare(plan)  # allocations happen here, not under capture
+    bufs = upload(V, dev)
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    torch.cuda.synchronize()
+    say("capturing")
+    with torch.cuda.graph(graph, stream=side):
+        D.ddl_allreduce_sim(bufs, P, plan, count, D.DDL_F32, torch.cuda.current_stream())
+    for replay in range(3):
+        say(f"replay {replay}")
+        for b, v in zip(bufs, V):           # eager work between replays: restore the inputs
+            b.copy_(torch.from_numpy(v))
+        torch.cuda.synchronize()
+        graph.replay()
+        for j, g in enumerate(download(bufs)):
+            assert_bitwise(g, want[j], f"replay {replay} learner={j}")
+
+
 def test_buffers_as_aligned_views_of_one_allocation(dev):
     dims, count, P = [2, 2], 10007, 4
     stride = 10240  # elements; multiple of 4 -> 16-byte aligned views, non-overlapping

@@ -145,7 +145,8 @@ def test_call_argument_errors(entry):
 
 def test_fused_limits_and_bytes():
     plan = D.ddl_ring_plan([4, 8, 8], 256, 25557032)
-    assert D.ddl_plan_fused_bytes(plan) == 8 * 25557032 * 256
+    assert D.ddl_plan_fused_bytes(plan) == 4 * 25557032 * (2 * 256 + 2)
+    assert D.ddl_plan_fused_bytes(D.ddl_ring_plan([4, 4], 16, 1000)) == 4 * 1000 * 32
     assert D.ddl_plan_fused_bytes(None) == 0
     # rejected on the host, before any device work: too many learners / too many levels
     big = D.ddl_ring_plan([2048], 2048, 64)
