@@ -32,6 +32,8 @@ def main():
     ap.add_argument("--profile-passes", type=int, default=10)
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
     ap.add_argument("--no-fused", action="store_true", help="skip timing the step-fused variant")
+    ap.add_argument("--per-tensor", action="store_true",
+                    help="also time the per-tensor mode (always done for the per-layer configuration)")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="also run one plain device-to-device copy of this many MiB (a dispatch of "
                          "known size, to scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
@@ -110,6 +112,33 @@ def main():
                      "speedup_vs_schedule": ms_per_step / f_ms}
         except D.DdlError as e:
             fused = {"entry": "ddl_allreduce_fused_sim", "error": str(e)}
+
+    # Per-tensor mode (each layer's tensor reduced on its own, all transfers of a phase in
+    # one launch): timed for the configuration that is defined as a per-layer tensor list,
+    # or on request; rated against its own schedule's bytes.
+    per_tensor = None
+    if args.per_tensor or "layers" in cfg["name"]:
+        shapes = I.resnet50_shapes() if count == I.RESNET50_COUNT else (
+            I.resnet101_22k_shapes() if count == I.RESNET101_22K_COUNT else None)
+        if shapes is not None:
+            offs, cnts = I.tensor_segments(shapes)
+            tplan = D.ddl_ring_plan_tensors(dims, P, offs, cnts, count)
+            D.ddl_plan_prepare(tplan)
+            for i in range(W):
+                D.ddl_allreduce_sim(sets[i % n_sets], P, tplan, count, D.DDL_F32, stream)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for i in range(W, W + K):
+                D.ddl_allreduce_sim(sets[i % n_sets], P, tplan, count, D.DDL_F32, stream)
+            torch.cuda.synchronize()
+            t_ms = (time.perf_counter() - t0) * 1e3 / K
+            t_bytes = D.ddl_plan_bytes_moved(tplan)
+            per_tensor = {"entry": "ddl_ring_plan_tensors + ddl_allreduce_sim", "tensors": len(offs),
+                          "ms_per_step": t_ms, "GBs_per_virtual_learner": 4 * count / (t_ms * 1e-3) / 1e9,
+                          "bytes": t_bytes, "achieved_GBs": t_bytes / (t_ms * 1e-3) / 1e9,
+                          "frac": t_bytes / (t_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                          "slowdown_vs_one_buffer": t_ms / ms_per_step}
+            del tplan
 
     # quick self-check on the last set used: every learner holds the same bits
     last = sets[(W + K - 1) % n_sets]
@@ -211,6 +240,7 @@ def main():
         "learners_identical": bool(same),
         "roofline": roofline,
         "fused_variant": fused,
+        "per_tensor_variant": per_tensor,
         "cpu_baseline": cpu,
     }
     print(json.dumps(out))

@@ -67,6 +67,7 @@ enum { DDL_STEP_REDUCE = 0, DDL_STEP_GATHER = 1 };
 /* Largest supported number of learners and box dimensions. */
 #define DDL_MAX_LEARNERS 65535
 #define DDL_MAX_DIMS 16
+#define DDL_MAX_TENSORS 65536
 
 /*
  * Build the schedule for a box dims[0..m-1] (Sec. 4.3: N = d_1*...*d_m) over P learners
@@ -76,6 +77,21 @@ enum { DDL_STEP_REDUCE = 0, DDL_STEP_GATHER = 1 };
  */
 ddl_plan_t* ddl_ring_plan(const int* dims, int m, int P, size_t count, ddl_dtype_t dtype,
                           ddl_status_t* status);
+
+/*
+ * The same for a buffer that holds several tensors, each reduced on its own (a network's
+ * gradients are a list of per-layer tensors; Sec. 4.1: an object wraps "a tensor of
+ * gradients").  Tensor s occupies elements [tensor_off[s], tensor_off[s] + tensor_count[s])
+ * of every learner's buffer of `count` elements; tensors must be given in ascending order,
+ * must not overlap, and must start on 16-byte granules (DDL_ERR_ALIGN otherwise).  Every
+ * tensor is chunked by itself (tiny tensors give empty chunks), but all transfers of one
+ * phase, over all tensors, are batched into one kernel launch.  Elements outside every
+ * tensor are never touched.  The plan is used with the same ddl_*_sim entry points;
+ * ddl_allreduce_fused_sim does not serve it (DDL_ERR_UNSUPPORTED).
+ */
+ddl_plan_t* ddl_ring_plan_tensors(const int* dims, int m, int P, const size_t* tensor_off,
+                                  const size_t* tensor_count, int num_tensors, size_t count,
+                                  ddl_dtype_t dtype, ddl_status_t* status);
 
 /* Free a plan and its device tables.  NULL is a no-op.  The caller must make sure no
  * enqueued work still uses the plan (synchronise the streams first). */
@@ -183,15 +199,24 @@ size_t ddl_plan_step_bytes(const ddl_plan_t* plan, int step);
 
 /*
  * Describe step `step` (0-based).  *kind = DDL_STEP_REDUCE / DDL_STEP_GATHER, *dim = the
- * 0-based box dimension whose rings run; src/dst/off/n are caller arrays of P entries
- * (any may be NULL), filled in order of the sending learner: operation i reads
- * [off[i], off[i]+n[i]) of learner src[i] = i and targets the same range of dst[i].
+ * 0-based box dimension whose rings run; src/dst/off/n are caller arrays of
+ * P * ddl_plan_num_tensors entries (any may be NULL), filled tensor by tensor and, within a
+ * tensor, in order of the sending learner: operation i reads [off[i], off[i]+n[i]) of
+ * learner src[i] = i mod P and targets the same range of dst[i].
  */
 ddl_status_t ddl_plan_get_step(const ddl_plan_t* plan, int step, int* kind, int* dim,
                                int* src, int* dst, size_t* off, size_t* n);
 
-/* The finest chunk learner `learner` owns after the reduce-scatter: [*off, *off + *n). */
+/* The finest chunk learner `learner` owns after the reduce-scatter: [*off, *off + *n)
+ * (of tensor 0 for a several-tensor plan). */
 ddl_status_t ddl_plan_owned_chunk(const ddl_plan_t* plan, int learner, size_t* off, size_t* n);
+
+/* Tensors of the plan: 1 for ddl_ring_plan, num_tensors for ddl_ring_plan_tensors, 0 for NULL. */
+int ddl_plan_num_tensors(const ddl_plan_t* plan);
+
+/* The finest chunk of tensor `tensor` that `learner` owns, offset relative to the buffer. */
+ddl_status_t ddl_plan_owned_chunk_tensor(const ddl_plan_t* plan, int tensor, int learner, size_t* off,
+                                         size_t* n);
 
 /*
  * Estimated time on a cluster, seconds (Sec. 4.3: T ~ sum_{j=1}^{d-1} (S/(d*B) + L) per

@@ -19,6 +19,8 @@ from .ddl_oracle import (  # noqa: F401
     allreduce_fold,
     allreduce_fold_range,
     sum_fp64,
+    schedule_tensors,
+    allreduce_tensors,
     bf16_add,
     bf16_to_f32,
     f32_to_bf16,

@@ -298,6 +298,38 @@ def bf16_add(x: np.ndarray, y: np.ndarray) -> np.ndarray:
     return f32_to_bf16(bf16_to_f32(x) + bf16_to_f32(y))
 
 
+# --------------------------------------------------------------------------------------
+# Several tensors per learner, each reduced on its own (the gradients of a network are a
+# list of per-layer tensors, Sec. 4.1: a DDL object wraps "a tensor of gradients")
+# --------------------------------------------------------------------------------------
+def schedule_tensors(dims, segments, G: int) -> list:
+    """Phases when every tensor (off, n) of `segments` is chunked and reduced by itself but
+    the transfers of one phase are issued together: ops of all tensors, tensor-major,
+    with offsets relative to the whole buffer."""
+    per_tensor = [schedule(dims, n, G) for _, n in segments]
+    steps = []
+    for i in range(2 * sum(d - 1 for d in dims)):
+        kind, t = ("RS", 0), None
+        ops = []
+        for (off, _), sched in zip(segments, per_tensor):
+            kind, t, tensor_ops = sched[i]
+            ops += [(src, dst, off + a, off + b) for src, dst, a, b in tensor_ops]
+        steps.append((kind, t, ops))
+    return steps
+
+
+def allreduce_tensors(V, dims, segments, add=None) -> list:
+    """The plain definition of the per-tensor mode: run the single-tensor allreduce on
+    every tensor's slice; elements outside all tensors are left alone."""
+    _check_inputs(V, dims)
+    out = [np.array(v, copy=True) for v in V]
+    for off, n in segments:
+        part = allreduce_steps([v[off:off + n] for v in V], dims, add)
+        for o, p in zip(out, part):
+            o[off:off + n] = p
+    return out
+
+
 def sum_fp64(V) -> np.ndarray:
     """Form (iii): R = sum_j V_j in double precision, learners in rank order."""
     acc = np.zeros(len(V[0]), dtype=np.float64)

@@ -14,7 +14,8 @@ _BINDING_NAMES = (
     "DDL_ERR_PLAN_MISMATCH", "DDL_ERR_NOMEM", "DDL_ERR_HIP", "DDL_ERR_UNSUPPORTED",
     "DDL_STEP_REDUCE", "DDL_STEP_GATHER",
     "DdlError", "Plan",
-    "ddl_ring_plan", "ddl_plan_free", "ddl_plan_prepare",
+    "ddl_ring_plan", "ddl_ring_plan_tensors", "ddl_plan_free", "ddl_plan_prepare",
+    "ddl_plan_num_tensors", "ddl_plan_owned_chunk_tensor",
     "ddl_allreduce_sim", "ddl_reduce_scatter_sim", "ddl_allgather_sim",
     "ddl_allreduce_sim_profile", "ddl_allreduce_sim_timed", "ddl_allreduce_fused_sim",
     "ddl_plan_fused_bytes",

@@ -28,6 +28,9 @@ def _load():
     sim_args = [ctypes.POINTER(vp), i, vp, sz, i, vp]
     sigs = {
         "ddl_ring_plan": (vp, [pi, i, i, sz, i, pi]),
+        "ddl_ring_plan_tensors": (vp, [pi, i, i, psz, psz, i, sz, i, pi]),
+        "ddl_plan_num_tensors": (i, [vp]),
+        "ddl_plan_owned_chunk_tensor": (i, [vp, i, i, psz, psz]),
         "ddl_plan_free": (None, [vp]),
         "ddl_plan_prepare": (i, [vp]),
         "ddl_allreduce_sim": (i, sim_args),
@@ -108,6 +111,30 @@ def ddl_ring_plan(dims, P, count, dtype=DDL_F32):
     return Plan(handle, dims, P, count, dtype)
 
 
+def ddl_ring_plan_tensors(dims, P, tensor_off, tensor_count, count, dtype=DDL_F32):
+    """Plan for a buffer of `count` elements holding several independently reduced tensors."""
+    arr = (ctypes.c_int * max(len(dims), 1))(*dims)
+    S = len(tensor_off)
+    offs = (ctypes.c_size_t * max(S, 1))(*tensor_off)
+    cnts = (ctypes.c_size_t * max(S, 1))(*tensor_count)
+    status = ctypes.c_int(0)
+    handle = _lib.ddl_ring_plan_tensors(arr, len(dims), P, offs, cnts, S, count, dtype, ctypes.byref(status))
+    if not handle:
+        raise DdlError(status.value, "ddl_ring_plan_tensors")
+    return Plan(handle, dims, P, count, dtype)
+
+
+def ddl_plan_num_tensors(plan):
+    return _lib.ddl_plan_num_tensors(_h(plan))
+
+
+def ddl_plan_owned_chunk_tensor(plan, tensor, learner):
+    off, n = ctypes.c_size_t(0), ctypes.c_size_t(0)
+    _check(_lib.ddl_plan_owned_chunk_tensor(_h(plan), tensor, learner, ctypes.byref(off), ctypes.byref(n)),
+           "ddl_plan_owned_chunk_tensor")
+    return off.value, n.value
+
+
 def ddl_plan_free(plan):
     if isinstance(plan, Plan):
         if plan.handle:
@@ -185,7 +212,7 @@ def ddl_plan_step_bytes(plan, step):
 
 def ddl_plan_get_step(plan, step):
     """Returns (kind, dim, [(src, dst, off, n), ...])."""
-    P = max(ddl_plan_num_learners(plan), 1)
+    P = max(ddl_plan_num_learners(plan) * max(ddl_plan_num_tensors(plan), 1), 1)
     kind, dim = ctypes.c_int(-1), ctypes.c_int(-1)
     src, dst = (ctypes.c_int * P)(), (ctypes.c_int * P)()
     off, n = (ctypes.c_size_t * P)(), (ctypes.c_size_t * P)()

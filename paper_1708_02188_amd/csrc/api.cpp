@@ -45,10 +45,21 @@ ddl_status_t device_tables(const ddl_plan* plan, DeviceTables* out) {
             return DDL_ERR_NOMEM;
         }
     }
+    if (!plan->descs.empty()) {
+        const size_t bytes = plan->descs.size() * sizeof(ddl::BlockDesc);
+        if (hipMalloc(reinterpret_cast<void**>(&t.descs), bytes) != hipSuccess ||
+            hipMemcpy(t.descs, plan->descs.data(), bytes, hipMemcpyHostToDevice) != hipSuccess) {
+            if (t.descs) (void)hipFree(t.descs);
+            if (t.ops) (void)hipFree(t.ops);
+            if (t.rops) (void)hipFree(t.rops);
+            return DDL_ERR_NOMEM;
+        }
+    }
     if (plan->P > ddl::kKernargLearners) {
         if (hipMalloc(reinterpret_cast<void**>(&t.ptrs), size_t(plan->P) * sizeof(void*)) != hipSuccess) {
             if (t.ops) (void)hipFree(t.ops);
             if (t.rops) (void)hipFree(t.rops);
+            if (t.descs) (void)hipFree(t.descs);
             return DDL_ERR_NOMEM;
         }
     }
@@ -155,19 +166,17 @@ ddl_status_t run_steps(void** bufs, int P, const ddl_plan* plan, size_t count, d
     }
     if (events && hipEventRecord(events[0], stream) != hipSuccess) return DDL_ERR_HIP;
     for (int s = first; s < last; ++s) {
-        if (ddl::launch_step(*plan, plan->steps[s], tables.rops + size_t(s) * P, stream) != hipSuccess)
+        const size_t per_step = size_t(P) * plan->seg_off.size();
+        if (ddl::launch_step(*plan, plan->steps[s], tables.rops + size_t(s) * per_step, tables.descs,
+                             stream) != hipSuccess)
             return DDL_ERR_HIP;
         if (events && hipEventRecord(events[s - first + 1], stream) != hipSuccess) return DDL_ERR_HIP;
     }
     return DDL_OK;
 }
 
-}  // namespace
-
-extern "C" {
-
-ddl_plan_t* ddl_ring_plan(const int* dims, int m, int P, size_t count, ddl_dtype_t dtype,
-                          ddl_status_t* status) {
+ddl_plan_t* make_plan(const int* dims, int m, int P, const size_t* seg_off, const size_t* seg_count,
+                      int S, size_t count, ddl_dtype_t dtype, ddl_status_t* status) {
     const int elem = ddl::dtype_size(dtype);
     if (elem == 0) {
         set_status(status, DDL_ERR_DTYPE);
@@ -175,6 +184,15 @@ ddl_plan_t* ddl_ring_plan(const int* dims, int m, int P, size_t count, ddl_dtype
     }
     ddl_status_t st = ddl::validate_dims(dims, m, P);
     if (st == DDL_OK && count > (uint64_t(1) << 56)) st = DDL_ERR_ARG;
+    if (st == DDL_OK && (S < 1 || S > DDL_MAX_TENSORS || seg_off == nullptr || seg_count == nullptr))
+        st = DDL_ERR_ARG;
+    const uint64_t G = 16 / uint64_t(elem);
+    uint64_t end = 0;  // tensors ascending, disjoint, inside the buffer, starts on 16-byte granules
+    for (int s = 0; st == DDL_OK && s < S; ++s) {
+        if (seg_off[s] % G != 0) st = DDL_ERR_ALIGN;
+        else if (seg_off[s] < end || seg_count[s] > count || seg_off[s] > count - seg_count[s]) st = DDL_ERR_ARG;
+        end = seg_off[s] + seg_count[s];
+    }
     if (st != DDL_OK) {
         set_status(status, st);
         return nullptr;
@@ -187,6 +205,8 @@ ddl_plan_t* ddl_ring_plan(const int* dims, int m, int P, size_t count, ddl_dtype
         plan->count = count;
         plan->dtype = dtype;
         plan->elem_size = elem;
+        plan->seg_off.assign(seg_off, seg_off + S);
+        plan->seg_count.assign(seg_count, seg_count + S);
         ddl::build_schedule(plan);
     } catch (const std::bad_alloc&) {
         delete plan;
@@ -197,12 +217,29 @@ ddl_plan_t* ddl_ring_plan(const int* dims, int m, int P, size_t count, ddl_dtype
     return plan;
 }
 
+}  // namespace
+
+extern "C" {
+
+ddl_plan_t* ddl_ring_plan(const int* dims, int m, int P, size_t count, ddl_dtype_t dtype,
+                          ddl_status_t* status) {
+    const size_t off = 0;
+    return make_plan(dims, m, P, &off, &count, 1, count, dtype, status);
+}
+
+ddl_plan_t* ddl_ring_plan_tensors(const int* dims, int m, int P, const size_t* tensor_off,
+                                  const size_t* tensor_count, int num_tensors, size_t count,
+                                  ddl_dtype_t dtype, ddl_status_t* status) {
+    return make_plan(dims, m, P, tensor_off, tensor_count, num_tensors, count, dtype, status);
+}
+
 void ddl_plan_free(ddl_plan_t* plan) {
     if (plan == nullptr) return;
     for (const DeviceTables& t : plan->tables) {
         if (t.ops) (void)hipFree(t.ops);
         if (t.rops) (void)hipFree(t.rops);
         if (t.ptrs) (void)hipFree(t.ptrs);
+        if (t.descs) (void)hipFree(t.descs);
         if (t.fused_seq) (void)hipFree(t.fused_seq);
         if (t.fused_ctl) (void)hipFree(t.fused_ctl);
         if (t.fused_n) (void)hipFree(t.fused_n);
@@ -243,7 +280,8 @@ ddl_status_t ddl_allreduce_fused_sim(void** bufs, int P, const ddl_plan_t* plan,
     if (st != DDL_OK) return st;
     int levels = 0;
     for (int d : plan->dims) levels += d > 1;
-    if (P > DDL_FUSED_MAX_LEARNERS || levels > DDL_FUSED_MAX_LEVELS) return DDL_ERR_UNSUPPORTED;
+    if (P > DDL_FUSED_MAX_LEARNERS || levels > DDL_FUSED_MAX_LEVELS || plan->seg_off.size() != 1)
+        return DDL_ERR_UNSUPPORTED;
     if (count == 0 || levels == 0) return DDL_OK;
     hipStream_t stream = static_cast<hipStream_t>(stream_v);
     DeviceTables t;
@@ -365,8 +403,9 @@ ddl_status_t ddl_plan_get_step(const ddl_plan_t* plan, int step, int* kind, int*
     const ddl::Step& st = plan->steps[step];
     if (kind) *kind = st.kind;
     if (dim) *dim = st.dim;
-    const Op* ops = plan->ops.data() + size_t(step) * plan->P;
-    for (int i = 0; i < plan->P; ++i) {
+    const size_t per_step = size_t(plan->P) * plan->seg_off.size();
+    const Op* ops = plan->ops.data() + size_t(step) * per_step;
+    for (size_t i = 0; i < per_step; ++i) {
         if (src) src[i] = ops[i].src;
         if (dst) dst[i] = ops[i].dst;
         if (off) off[i] = ops[i].off;
@@ -375,11 +414,22 @@ ddl_status_t ddl_plan_get_step(const ddl_plan_t* plan, int step, int* kind, int*
     return DDL_OK;
 }
 
-ddl_status_t ddl_plan_owned_chunk(const ddl_plan_t* plan, int learner, size_t* off, size_t* n) {
-    if (plan == nullptr || learner < 0 || learner >= plan->P) return DDL_ERR_ARG;
-    if (off) *off = plan->own_off[learner];
-    if (n) *n = plan->own_n[learner];
+int ddl_plan_num_tensors(const ddl_plan_t* plan) {
+    return plan ? static_cast<int>(plan->seg_off.size()) : 0;
+}
+
+ddl_status_t ddl_plan_owned_chunk_tensor(const ddl_plan_t* plan, int tensor, int learner, size_t* off,
+                                         size_t* n) {
+    if (plan == nullptr || learner < 0 || learner >= plan->P || tensor < 0 ||
+        tensor >= static_cast<int>(plan->seg_off.size()))
+        return DDL_ERR_ARG;
+    if (off) *off = plan->own_off[size_t(tensor) * plan->P + learner];
+    if (n) *n = plan->own_n[size_t(tensor) * plan->P + learner];
     return DDL_OK;
+}
+
+ddl_status_t ddl_plan_owned_chunk(const ddl_plan_t* plan, int learner, size_t* off, size_t* n) {
+    return ddl_plan_owned_chunk_tensor(plan, 0, learner, off, n);
 }
 
 double ddl_plan_model_time(const ddl_plan_t* plan, const double* bw, const double* lat) {

@@ -20,10 +20,11 @@ struct PtrTable {
 hipError_t launch_resolve(const ddl_plan& plan, const Op* d_ops, ResolvedOp* d_rops,
                           const PtrTable& table, void* const* d_ptrs, hipStream_t stream);
 
-// Enqueue the kernel of one step.  d_rops points at that step's P resolved operations in
-// device memory.  A step that moves nothing enqueues nothing.
+// Enqueue the kernel of one step.  d_rops points at that step's resolved operations in
+// device memory; d_descs at the plan's work list (several-tensor plans, else unused).
+// A step that moves nothing enqueues nothing.
 hipError_t launch_step(const ddl_plan& plan, const Step& step, const ResolvedOp* d_rops,
-                       hipStream_t stream);
+                       const BlockDesc* d_descs, hipStream_t stream);
 
 // Step-fused allreduce.  launch_fused_resolve binds the summation-order table to the
 // caller's buffers: d_ptrs_out[c * padded + i] = address of finest chunk c in learner

@@ -154,12 +154,60 @@ typedef uint64_t u64x4 __attribute__((ext_vector_type(4)));
 constexpr uint64_t kRowBytes = 1024;
 constexpr uint64_t kRowVecs = kRowBytes / 16;
 
+// One tile of one operation: DDL_THREADS * DDL_UNROLL vectors starting at vector index
+// `first` of the row-aligned tiling (first may be negative or reach past the end at the
+// edges of the operation).
+template <typename T, bool REDUCE>
+__device__ __forceinline__ void step_tile(const DDL_GLOBAL typename Elem<T>::V* src,
+                                          DDL_GLOBAL typename Elem<T>::V* dst, int64_t n, int64_t nv,
+                                          int64_t first, int64_t tid) {
+    typedef typename Elem<T>::V V;
+    typedef typename Elem<T>::S S;
+    constexpr int64_t VL = 16 / sizeof(S);
+    constexpr int64_t TILE = int64_t(DDL_THREADS) * DDL_UNROLL;
+    if (first >= 0 && first + TILE <= nv) {
+        const DDL_GLOBAL V* s = src + first + tid;
+        DDL_GLOBAL V* d = dst + first + tid;
+        V a[DDL_UNROLL];
+        V b[DDL_UNROLL];
+#pragma unroll
+        for (int u = 0; u < DDL_UNROLL; ++u) a[u] = stream_load(s + u * DDL_THREADS);
+        if (REDUCE) {
+#pragma unroll
+            for (int u = 0; u < DDL_UNROLL; ++u) b[u] = stream_load(d + u * DDL_THREADS);
+#pragma unroll
+            for (int u = 0; u < DDL_UNROLL; ++u) a[u] = Elem<T>::add(b[u], a[u]);
+        }
+#pragma unroll
+        for (int u = 0; u < DDL_UNROLL; ++u) stream_store(d + u * DDL_THREADS, a[u]);
+    } else {
+        // first or last tile of the operation: per-lane bounds
+#pragma unroll
+        for (int u = 0; u < DDL_UNROLL; ++u) {
+            const int64_t v = first + u * DDL_THREADS + tid;
+            if (v >= 0 && v < nv) {
+                V a = src[v];
+                if (REDUCE) a = Elem<T>::add(dst[v], a);
+                dst[v] = a;
+            } else if (v == nv) {
+                // the buffer's last, short vector: element by element
+                const DDL_GLOBAL S* se = (const DDL_GLOBAL S*)(src + nv);
+                DDL_GLOBAL S* de = (DDL_GLOBAL S*)(dst + nv);
+                for (int64_t e = 0; e < n - nv * VL; ++e) {
+                    S a = se[e];
+                    if (REDUCE) a = Elem<T>::add1(de[e], a);
+                    de[e] = a;
+                }
+            }
+        }
+    }
+}
+
 template <typename T, bool REDUCE>
 __global__ __launch_bounds__(DDL_THREADS) void step_kernel(const ResolvedOp* __restrict__ rops,
                                                            unsigned tile_stride) {
     typedef typename Elem<T>::V V;
-    typedef typename Elem<T>::S S;
-    constexpr int64_t VL = 16 / sizeof(S);                          // elements per vector
+    constexpr int64_t VL = 16 / sizeof(typename Elem<T>::S);        // elements per vector
     constexpr int64_t TILE = int64_t(DDL_THREADS) * DDL_UNROLL;     // vectors per tile
 
     // the whole record in one scalar load: {src address, dst address, n, -}
@@ -169,47 +217,50 @@ __global__ __launch_bounds__(DDL_THREADS) void step_kernel(const ResolvedOp* __r
     const int64_t n = int64_t(rec.z);
     const int64_t nv = n / VL;                                      // whole vectors
     const int64_t shift = int64_t((rec.y % kRowBytes) / 16);        // vectors past a row boundary
-    const int64_t tid = threadIdx.x;
 
     // vector index v of the operation <-> slot v + shift of the row-aligned tiling
-    for (int64_t first = int64_t(blockIdx.x) * TILE - shift; first <= nv; first += int64_t(tile_stride) * TILE) {
-        if (first >= 0 && first + TILE <= nv) {
-            const DDL_GLOBAL V* s = src + first + tid;
-            DDL_GLOBAL V* d = dst + first + tid;
-            V a[DDL_UNROLL];
-            V b[DDL_UNROLL];
-#pragma unroll
-            for (int u = 0; u < DDL_UNROLL; ++u) a[u] = stream_load(s + u * DDL_THREADS);
-            if (REDUCE) {
-#pragma unroll
-                for (int u = 0; u < DDL_UNROLL; ++u) b[u] = stream_load(d + u * DDL_THREADS);
-#pragma unroll
-                for (int u = 0; u < DDL_UNROLL; ++u) a[u] = Elem<T>::add(b[u], a[u]);
-            }
-#pragma unroll
-            for (int u = 0; u < DDL_UNROLL; ++u) stream_store(d + u * DDL_THREADS, a[u]);
-        } else {
-            // first or last tile of the operation: per-lane bounds
-#pragma unroll
-            for (int u = 0; u < DDL_UNROLL; ++u) {
-                const int64_t v = first + u * DDL_THREADS + tid;
-                if (v >= 0 && v < nv) {
-                    V a = src[v];
-                    if (REDUCE) a = Elem<T>::add(dst[v], a);
-                    dst[v] = a;
-                } else if (v == nv) {
-                    // the buffer's last, short vector: element by element
-                    const DDL_GLOBAL S* se = (const DDL_GLOBAL S*)(src + nv);
-                    DDL_GLOBAL S* de = (DDL_GLOBAL S*)(dst + nv);
-                    for (int64_t e = 0; e < n - nv * VL; ++e) {
-                        S a = se[e];
-                        if (REDUCE) a = Elem<T>::add1(de[e], a);
-                        de[e] = a;
-                    }
-                }
-            }
-        }
+    for (int64_t first = int64_t(blockIdx.x) * TILE - shift; first <= nv; first += int64_t(tile_stride) * TILE)
+        step_tile<T, REDUCE>(src, dst, n, nv, first, threadIdx.x);
+}
+
+// Several-tensor plans: the phase's transfers differ in length by orders of magnitude, so
+// the launch is a flat list of work items (operation, first row); a workgroup of four
+// waves takes the kListRows rows of its item, one row per wave at a time.
+template <typename T, bool REDUCE>
+__global__ __launch_bounds__(256) void step_kernel_list(const ResolvedOp* __restrict__ rops,
+                                                        const BlockDesc* __restrict__ descs) {
+    static_assert(DDL_THREADS * DDL_UNROLL == 64, "a row is one wave's worth of vectors");
+    typedef typename Elem<T>::V V;
+    constexpr int64_t VL = 16 / sizeof(typename Elem<T>::S);
+    const BlockDesc item = descs[blockIdx.x];
+    const u64x4 rec = *reinterpret_cast<const u64x4*>(rops + item.op);
+    const DDL_GLOBAL V* src = (const DDL_GLOBAL V*)rec.x;
+    DDL_GLOBAL V* dst = (DDL_GLOBAL V*)rec.y;
+    const int64_t n = int64_t(rec.z);
+    const int64_t nv = n / VL;
+    const int64_t shift = int64_t((rec.y % kRowBytes) / 16);
+    const int wave = threadIdx.x / 64;
+    const int64_t lane = threadIdx.x % 64;
+    for (int k = wave; k < kListRows; k += 4) {
+        const int64_t first = (int64_t(item.row) + k) * 64 - shift;
+        if (first > nv) break;
+        step_tile<T, REDUCE>(src, dst, n, nv, first, lane);
     }
+}
+
+template <typename T>
+hipError_t launch_list_typed(const Step& step, const ResolvedOp* d_rops, const BlockDesc* d_descs,
+                             hipStream_t stream) {
+    if (step.desc_count == 0) return hipSuccess;
+    if (step.desc_count > 0x7FFFFFFFull) return hipErrorInvalidValue;
+    const dim3 grid(static_cast<unsigned>(step.desc_count), 1, 1);
+    if (step.kind == DDL_STEP_REDUCE)
+        hipLaunchKernelGGL((step_kernel_list<T, true>), grid, dim3(256), 0, stream, d_rops,
+                           d_descs + step.desc_first);
+    else
+        hipLaunchKernelGGL((step_kernel_list<T, false>), grid, dim3(256), 0, stream, d_rops,
+                           d_descs + step.desc_first);
+    return hipGetLastError();
 }
 
 template <typename T>
@@ -370,8 +421,18 @@ hipError_t launch_resolve(const ddl_plan& plan, const Op* d_ops, ResolvedOp* d_r
 }
 
 hipError_t launch_step(const ddl_plan& plan, const Step& step, const ResolvedOp* d_rops,
-                       hipStream_t stream) {
+                       const BlockDesc* d_descs, hipStream_t stream) {
     if (step.max_n == 0) return hipSuccess;
+    if (plan.seg_off.size() > 1) {
+        switch (plan.dtype) {
+            case DDL_F32: return launch_list_typed<float>(step, d_rops, d_descs, stream);
+            case DDL_F64: return launch_list_typed<double>(step, d_rops, d_descs, stream);
+            case DDL_I32: return launch_list_typed<unsigned>(step, d_rops, d_descs, stream);
+            case DDL_F16: return launch_list_typed<_Float16>(step, d_rops, d_descs, stream);
+            case DDL_BF16: return launch_list_typed<bf16_bits>(step, d_rops, d_descs, stream);
+        }
+        return hipErrorInvalidValue;
+    }
     switch (plan.dtype) {
         case DDL_F32: return launch_typed<float>(plan, step, d_rops, stream);
         case DDL_F64: return launch_typed<double>(plan, step, d_rops, stream);

@@ -43,45 +43,71 @@ void split_range(uint64_t lo, uint64_t hi, uint64_t d, uint64_t k, uint64_t G,
 void build_schedule(ddl_plan* plan) {
     const int m = static_cast<int>(plan->dims.size());
     const int P = plan->P;
+    const int S = static_cast<int>(plan->seg_off.size());
     const uint64_t G = 16 / static_cast<uint64_t>(plan->elem_size);
 
-    // Segment every learner works on at the start of each dimension (level 0 = everything).
-    std::vector<std::vector<uint64_t>> lo(m + 1, std::vector<uint64_t>(P, 0));
-    std::vector<std::vector<uint64_t>> hi(m + 1, std::vector<uint64_t>(P, plan->count));
     std::vector<int> stride(m + 1, 1);  // rank distance of one position along dimension t
-    for (int t = 0; t < m; ++t) {
-        const int d = plan->dims[t];
-        stride[t + 1] = stride[t] * d;
+    for (int t = 0; t < m; ++t) stride[t + 1] = stride[t] * plan->dims[t];
+
+    // Segment every learner works on at the start of each dimension, per tensor
+    // (level 0 = the whole tensor); index [(s * (m + 1) + t) * P + r].
+    std::vector<uint64_t> lo(size_t(S) * (m + 1) * P), hi(lo.size());
+    auto at = [&](int s, int t, int r) { return (size_t(s) * (m + 1) + t) * P + r; };
+    for (int s = 0; s < S; ++s) {
         for (int r = 0; r < P; ++r) {
-            const int pos = (r / stride[t]) % d;
-            split_range(lo[t][r], hi[t][r], d, pos, G, &lo[t + 1][r], &hi[t + 1][r]);
+            lo[at(s, 0, r)] = plan->seg_off[s];
+            hi[at(s, 0, r)] = plan->seg_off[s] + plan->seg_count[s];
+        }
+        for (int t = 0; t < m; ++t) {
+            const int d = plan->dims[t];
+            for (int r = 0; r < P; ++r) {
+                const int pos = (r / stride[t]) % d;
+                split_range(lo[at(s, t, r)], hi[at(s, t, r)], d, pos, G, &lo[at(s, t + 1, r)],
+                            &hi[at(s, t + 1, r)]);
+            }
         }
     }
-    plan->own_off.assign(lo[m].begin(), lo[m].end());
-    plan->own_n.resize(P);
-    for (int r = 0; r < P; ++r) plan->own_n[r] = hi[m][r] - lo[m][r];
+    plan->own_off.resize(size_t(S) * P);
+    plan->own_n.resize(size_t(S) * P);
+    for (int s = 0; s < S; ++s)
+        for (int r = 0; r < P; ++r) {
+            plan->own_off[size_t(s) * P + r] = lo[at(s, m, r)];
+            plan->own_n[size_t(s) * P + r] = hi[at(s, m, r)] - lo[at(s, m, r)];
+        }
 
     auto emit = [&](int kind, int t, int phase) {
         const int d = plan->dims[t];
-        Step st{kind, t, 0, 0};
+        Step st{kind, t, 0, 0, plan->descs.size(), 0};
         const uint64_t per_elem = (kind == DDL_STEP_REDUCE ? 3u : 2u) * plan->elem_size;
-        for (int r = 0; r < P; ++r) {
-            const int pos = (r / stride[t]) % d;
-            const int next = r + ((pos + 1) % d - pos) * stride[t];
-            // reduce: in phase s ring position c passes on part c-s-1, the partial sum that
-            // set out one position after the part's owner; gather: position c passes on
-            // part c-s, its own completed part first.
-            const int back = (kind == DDL_STEP_REDUCE) ? phase + 1 : phase;
-            const int part = ((pos - back) % d + d) % d;
-            Op op;
-            split_range(lo[t][r], hi[t][r], d, part, G, &op.off, &op.n);
-            op.n -= op.off;
-            op.src = r;
-            op.dst = next;
-            if (op.n > st.max_n) st.max_n = op.n;
-            st.bytes += op.n * per_elem;
-            plan->ops.push_back(op);
+        for (int s = 0; s < S; ++s) {
+            for (int r = 0; r < P; ++r) {
+                const int pos = (r / stride[t]) % d;
+                const int next = r + ((pos + 1) % d - pos) * stride[t];
+                // reduce: in phase s ring position c passes on part c-s-1, the partial sum
+                // that set out one position after the part's owner; gather: position c
+                // passes on part c-s, its own completed part first.
+                const int back = (kind == DDL_STEP_REDUCE) ? phase + 1 : phase;
+                const int part = ((pos - back) % d + d) % d;
+                Op op;
+                split_range(lo[at(s, t, r)], hi[at(s, t, r)], d, part, G, &op.off, &op.n);
+                op.n -= op.off;
+                op.src = r;
+                op.dst = next;
+                if (op.n > st.max_n) st.max_n = op.n;
+                st.bytes += op.n * per_elem;
+                if (S > 1 && op.n > 0) {
+                    // work list for the batched launch: spans of kListRows 1 KiB rows; one
+                    // row more than the vectors need, because the tiling is shifted onto
+                    // absolute row boundaries at run time
+                    const uint64_t rows = (op.n / G + 1 + 63 + 63) / 64;
+                    const uint32_t index = static_cast<uint32_t>(plan->ops.size() % (size_t(S) * P));
+                    for (uint64_t row = 0; row < rows; row += kListRows)
+                        plan->descs.push_back(BlockDesc{index, static_cast<uint32_t>(row)});
+                }
+                plan->ops.push_back(op);
+            }
         }
+        st.desc_count = plan->descs.size() - st.desc_first;
         plan->bytes_total += st.bytes;
         plan->steps.push_back(st);
     };

@@ -30,11 +30,21 @@ struct ResolvedOp {
 };
 static_assert(sizeof(ResolvedOp) == 32, "one 32-byte scalar load per workgroup");
 
+// Work item of a phase of a several-tensor plan: rows [row, row + kListRows) of operation
+// `op` (index within the phase), a row being 64 lanes x 16 bytes.
+constexpr int kListRows = 16;
+struct BlockDesc {
+    uint32_t op;
+    uint32_t row;
+};
+
 struct Step {
-    int kind;        // DDL_STEP_REDUCE / DDL_STEP_GATHER
-    int dim;         // 0-based box dimension whose rings run in this phase
-    uint64_t max_n;  // longest operation of the phase (sizes the launch)
-    uint64_t bytes;  // memory traffic of the phase
+    int kind;           // DDL_STEP_REDUCE / DDL_STEP_GATHER
+    int dim;            // 0-based box dimension whose rings run in this phase
+    uint64_t max_n;     // longest operation of the phase (sizes the launch)
+    uint64_t bytes;     // memory traffic of the phase
+    size_t desc_first;  // several-tensor plans: this phase's slice of the work list
+    size_t desc_count;
 };
 
 // Tables of the step-fused allreduce.  Finest chunk c (owned by learner c) is summed over
@@ -52,6 +62,7 @@ struct DeviceTables {
     Op* ops = nullptr;           // num_steps * P operations, step-major
     ResolvedOp* rops = nullptr;  // the same operations bound to the buffers of the latest call
     void** ptrs = nullptr;       // staging for the learner pointers when P exceeds the kernarg table
+    BlockDesc* descs = nullptr;  // work list of a several-tensor plan
     // step-fused path, created at its first use
     uint32_t* fused_seq = nullptr;    // P * padded learner ranks
     uint32_t* fused_ctl = nullptr;    // padded control words
@@ -72,8 +83,10 @@ struct ddl_plan {
     int elem_size = 4;
     int first_gather = 0;                 // index of the first all-gather step
     std::vector<ddl::Step> steps;
-    std::vector<ddl::Op> ops;             // steps.size() * P, step-major, indexed by sender
-    std::vector<uint64_t> own_off, own_n; // finest chunk per learner
+    std::vector<uint64_t> seg_off, seg_count;  // the tensors inside every learner's buffer (S >= 1)
+    std::vector<ddl::Op> ops;             // steps.size() * S * P, step-major, then tensor, then sender
+    std::vector<ddl::BlockDesc> descs;    // work list, only when S > 1
+    std::vector<uint64_t> own_off, own_n; // finest chunk per (tensor, learner)
     uint64_t bytes_total = 0;
 
     mutable std::mutex mu;                      // guards `tables`

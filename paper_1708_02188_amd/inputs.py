@@ -91,6 +91,17 @@ def numel(shapes):
     return int(sum(int(np.prod(s)) for s in shapes))
 
 
+def tensor_segments(shapes):
+    """(offsets, counts) of the tensors laid end to end in definition order."""
+    offs, cnts, pos = [], [], 0
+    for shp in shapes:
+        n = int(np.prod(shp))
+        offs.append(pos)
+        cnts.append(n)
+        pos += n
+    return offs, cnts
+
+
 def resnet50_shapes():
     return resnet_shapes([3, 4, 6, 3], 1000)
 

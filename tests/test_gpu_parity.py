@@ -276,6 +276,88 @@ def test_more_learners_than_the_kernarg_table_holds(dev):
 
 
 # ---------------------------------------------------------------------------------------
+# several tensors per buffer, each reduced on its own, transfers batched per phase
+# ---------------------------------------------------------------------------------------
+TENSOR_CASES = [
+    ([4], [(0, 64), (64, 4), (68, 0), (72, 1000), (1072, 8), (1100, 37)], 1140),
+    ([2, 3], [(0, 5), (8, 3), (16, 100000)], 100016),
+    ([4, 4], [(0, 70000), (70000, 16), (70016, 4), (70020, 300000), (370020, 1)], 370021),
+    ([4, 2, 2], [(4 * i * 50, 150 + i) for i in range(40)] + [(8000, 262144 + 5)], 8000 + 262144 + 5),
+    ([3], [(0, 1), (4, 2), (8, 3)], 11),
+]
+
+
+@pytest.mark.parametrize("dims,segments,count", TENSOR_CASES)
+def test_tensor_plan_matches_per_tensor_oracle(dev, dims, segments, count):
+    P = prod(dims)
+    say(f"tensor plan dims={dims} tensors={len(segments)} count={count}")
+    rng = np.random.default_rng(600 + count)
+    V = wide_inputs(rng, P, count, D.DDL_F32)
+    bufs = upload(V, dev)
+    plan = D.ddl_ring_plan_tensors(dims, P, [o for o, _ in segments], [n for _, n in segments], count)
+    D.ddl_allreduce_sim(bufs, P, plan, count, D.DDL_F32, torch.cuda.current_stream())
+    got = download(bufs)
+    want = O.allreduce_tensors(V, dims, segments)   # gaps between tensors keep their input values
+    for j in range(P):
+        assert_bitwise(got[j], want[j], f"tensor plan dims={dims} learner={j}")
+    # the halves on their own
+    bufs = upload(V, dev)
+    D.ddl_reduce_scatter_sim(bufs, P, plan, count)
+    rs = download(bufs)
+    steps = O.schedule_tensors(dims, segments, 4)
+    want_rs = O._run([v.copy() for v in V], [st for st in steps if st[0] == "RS"])
+    for j in range(P):
+        assert_bitwise(rs[j], want_rs[j], f"tensor plan reduce-scatter learner={j}")
+    D.ddl_allgather_sim(bufs, P, plan, count)
+    for j, g in enumerate(download(bufs)):
+        assert_bitwise(g, want[j], f"tensor plan all-gather learner={j}")
+
+
+def test_tensor_plan_sixteen_bit(dev):
+    dims, P = [2, 2], 4
+    segments, count = [(0, 24), (24, 808), (832, 9), (848, 70001)], 848 + 70001
+    rng = np.random.default_rng(71)
+    V = wide_inputs(rng, P, count, D.DDL_BF16)
+    bufs = upload(V, dev)
+    plan = D.ddl_ring_plan_tensors(dims, P, [o for o, _ in segments], [n for _, n in segments], count, D.DDL_BF16)
+    D.ddl_allreduce_sim(bufs, P, plan, count, D.DDL_BF16)
+    want = O.allreduce_tensors(V, dims, segments, add=O.bf16_add)
+    for j, g in enumerate(download(bufs, np.uint16)):
+        assert_bitwise(g, want[j], f"bf16 tensor plan learner={j}")
+
+
+def test_config3_per_tensor_mode_full_size(dev):
+    """Configuration 3 as 161 independent per-layer allreduces (P=64, dims [4,16])."""
+    cfg = I.CONFIGS[2]
+    P, dims, count, dist, seed = cfg["P"], cfg["dims"], cfg["count"], cfg["dist"], cfg["seed"]
+    offs, cnts = I.tensor_segments(I.resnet50_shapes())
+    say(f"config 3 per-tensor: {len(offs)} tensors, smallest {min(cnts)}, largest {max(cnts)}")
+    bufs = [torch.empty(count, dtype=torch.float32, device=dev) for _ in range(P)]
+    for j, b in enumerate(bufs):
+        I.fill_device(b, seed, j, dist)
+    plan = D.ddl_ring_plan_tensors(dims, P, offs, cnts, count)
+    D.ddl_allreduce_sim(bufs, P, plan, count, D.DDL_F32, torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    for j in range(1, P):
+        assert torch.equal(bufs[0].view(torch.int32), bufs[j].view(torch.int32)), f"learner {j} differs"
+    got = bufs[0].cpu().numpy()
+    del bufs
+    torch.cuda.empty_cache()
+    # every small tensor whole, the large ones on sampled ranges
+    rng = np.random.default_rng(3)
+    checked = 0
+    for off, n in zip(offs, cnts):
+        ranges = [(0, n)] if n <= 8192 else [(0, 2048), (n - 2048, n)] + [
+            (int(a), int(a) + 1024) for a in rng.integers(0, n - 1024, 2)]
+        for a, b in ranges:
+            want = O.allreduce_fold_range(
+                lambda r, lo, hi: I.fill_host(hi - lo, seed, r, dist, first=off + lo), dims, n, a, b, np.float32)
+            assert_bitwise(got[off + a:off + b], want, f"tensor at {off} elements [{a},{b})")
+            checked += b - a
+    say(f"  {checked} elements checked against the oracle")
+
+
+# ---------------------------------------------------------------------------------------
 # step-fused allreduce: same final bits as the phase-by-phase schedule
 # ---------------------------------------------------------------------------------------
 FUSED_CASES = [([1], 100), ([2], 1), ([4], 37), ([4], 65536 + 5), ([3], 100003), ([2, 3], 50001), ([4, 4], 300007),

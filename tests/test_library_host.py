@@ -264,3 +264,47 @@ def test_choose_dims_matches_bruteforce_oracle():
     assert status_of(D.ddl_choose_dims, 0, 100, bw, [0.0] * 3) == D.DDL_ERR_ARG
     assert status_of(D.ddl_choose_dims, 4, 100, [0.0], [0.0]) == D.DDL_ERR_ARG
     assert status_of(D.ddl_choose_dims, 4, 100, [1.0], [-1.0]) == D.DDL_ERR_ARG
+
+
+# ---------------------------------------------------------------------------------------
+# several tensors per buffer
+# ---------------------------------------------------------------------------------------
+def test_tensor_plan_tables_equal_oracle_schedule():
+    cases = [
+        ([4], [(0, 64), (64, 4), (68, 0), (72, 1000), (1072, 8), (1100, 37)], 1140, D.DDL_F32, 4),
+        ([2, 3], [(0, 5), (8, 3), (16, 100000)], 100016, D.DDL_F32, 4),
+        ([4, 16], list(zip(*I.tensor_segments(I.resnet50_shapes()))), I.RESNET50_COUNT, D.DDL_F32, 4),
+        ([4, 2], [(0, 24), (24, 808), (832, 9)], 841, D.DDL_F16, 2),
+    ]
+    for dims, segments, count, dtype, itemsize in cases:
+        P = prod(dims)
+        G = 16 // itemsize
+        plan = D.ddl_ring_plan_tensors(dims, P, [o for o, _ in segments], [n for _, n in segments], count, dtype)
+        S = len(segments)
+        assert D.ddl_plan_num_tensors(plan) == S and D.ddl_plan_num_learners(plan) == P
+        steps = O.schedule_tensors(dims, segments, G)
+        assert D.ddl_plan_num_steps(plan) == len(steps)
+        total = 0
+        for i, (kind, t, ops) in enumerate(steps):
+            k, dim, lib_ops = D.ddl_plan_get_step(plan, i)
+            assert (k, dim) == (D.DDL_STEP_REDUCE if kind == "RS" else D.DDL_STEP_GATHER, t)
+            assert lib_ops == [(src, dst, a, b - a) for src, dst, a, b in ops]
+            total += sum(b - a for _, _, a, b in ops) * (3 if kind == "RS" else 2) * itemsize
+        assert D.ddl_plan_bytes_moved(plan) == total
+        for s_i, (off, n) in enumerate(segments):
+            for k, a, b in O.fine_chunks(dims, n, G):
+                assert D.ddl_plan_owned_chunk_tensor(plan, s_i, O.rank_of(k, dims)) == (off + a, b - a)
+
+
+def test_tensor_plan_argument_errors():
+    ok = dict(dims=[2, 2], P=4, count=100)
+    assert status_of(D.ddl_ring_plan_tensors, [2, 2], 4, [0, 10], [10, 10], 100) == D.DDL_ERR_ALIGN   # 10 % 4 != 0
+    assert status_of(D.ddl_ring_plan_tensors, [2, 2], 4, [0, 8], [10, 10], 100) == D.DDL_ERR_ARG     # overlap
+    assert status_of(D.ddl_ring_plan_tensors, [2, 2], 4, [16, 0], [4, 4], 100) == D.DDL_ERR_ARG      # not ascending
+    assert status_of(D.ddl_ring_plan_tensors, [2, 2], 4, [0, 96], [4, 8], 100) == D.DDL_ERR_ARG      # past the end
+    assert status_of(D.ddl_ring_plan_tensors, [2, 2], 4, [], [], 100) == D.DDL_ERR_ARG
+    assert status_of(D.ddl_ring_plan_tensors, [2, 3], 4, [0], [4], 100) == D.DDL_ERR_DIMS
+    plan = D.ddl_ring_plan_tensors([2, 2], 4, [0, 12], [12, 88], 100)
+    assert status_of(D.ddl_plan_owned_chunk_tensor, plan, 2, 0) == D.DDL_ERR_ARG
+    ptrs = [0x100000 + 0x1000 * j for j in range(4)]
+    assert status_of(D.ddl_allreduce_fused_sim, ptrs, 4, plan, 100) == D.DDL_ERR_UNSUPPORTED

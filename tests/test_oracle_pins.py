@@ -618,3 +618,38 @@ def test_sixteen_bit_types_bruteforce_and_forms_agree():
                 assert g.tobytes() == O.allreduce_fold(Vb, dims, add=O.bf16_add).tobytes()
     # chunks are cut on 16-byte granules = 8 elements
     assert O.granule(np.float16) == 8 and O.granule(np.uint16) == 8
+
+
+# ---------------------------------------------------------------------------------------
+# per-tensor mode
+# ---------------------------------------------------------------------------------------
+def test_per_tensor_mode_definition_and_batched_schedule_agree():
+    rng = np.random.default_rng(16)
+    segments = [(0, 64), (64, 4), (68, 0), (72, 1000), (1072, 8), (1100, 37)]  # gaps allowed
+    count = 1140
+    for dims in ([4], [2, 3], [4, 2, 2]):
+        P = prod(dims)
+        # integers: every tensor ends as the plain sum, the gaps are untouched
+        Vi = int_inputs(rng, P, count)
+        got = O.allreduce_tensors(Vi, dims, segments)
+        total = sum(v.astype(np.int64) for v in Vi)
+        covered = np.zeros(count, bool)
+        for off, n in segments:
+            covered[off:off + n] = True
+        for j in range(P):
+            assert np.array_equal(got[j][covered].astype(np.int64), total[covered])
+            assert np.array_equal(got[j][~covered], Vi[j][~covered])
+        # running the batched phase list gives the same bits as tensor-by-tensor
+        V = wide_fp32_inputs(rng, P, count)
+        want = O.allreduce_tensors(V, dims, segments)
+        bufs = O._run([v.copy() for v in V], O.schedule_tensors(dims, segments, 4))
+        for j in range(P):
+            assert bufs[j].tobytes() == want[j].tobytes()
+        # one tensor covering everything is the ordinary allreduce
+        one = O.allreduce_tensors(V, dims, [(0, count)])
+        for a, b in zip(one, O.allreduce_steps(V, dims)):
+            assert a.tobytes() == b.tobytes()
+        # phases: same count, P transfers per tensor and phase
+        steps = O.schedule_tensors(dims, segments, 4)
+        assert len(steps) == 2 * sum(d - 1 for d in dims)
+        assert all(len(ops) == P * len(segments) for _, _, ops in steps)
