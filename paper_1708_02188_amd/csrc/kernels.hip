@@ -224,27 +224,37 @@ __global__ __launch_bounds__(DDL_THREADS) void step_kernel(const ResolvedOp* __r
 }
 
 // Several-tensor plans: the phase's transfers differ in length by orders of magnitude, so
-// the launch is a flat list of work items (operation, first row); a workgroup of four
-// waves takes the kListRows rows of its item, one row per wave at a time.
+// the launch is a flat list of work items (operation, first row).  Items that hold all
+// kListRows rows come first and get one single-wave workgroup per row, like the
+// single-tensor kernel; the ragged last item of each operation gets four workgroups that
+// share its rows.
 template <typename T, bool REDUCE>
-__global__ __launch_bounds__(256) void step_kernel_list(const ResolvedOp* __restrict__ rops,
-                                                        const BlockDesc* __restrict__ descs) {
+__global__ __launch_bounds__(64) void step_kernel_list(const ResolvedOp* __restrict__ rops,
+                                                       const BlockDesc* __restrict__ descs,
+                                                       unsigned whole_blocks, unsigned whole_items,
+                                                       unsigned block_offset) {
     static_assert(DDL_THREADS * DDL_UNROLL == 64, "a row is one wave's worth of vectors");
     typedef typename Elem<T>::V V;
     constexpr int64_t VL = 16 / sizeof(typename Elem<T>::S);
-    const BlockDesc item = descs[blockIdx.x];
+    const unsigned b = blockIdx.x + block_offset;
+    const bool whole = b < whole_blocks;
+    const unsigned t = b - whole_blocks;
+    const BlockDesc item = descs[whole ? b / kListRows : whole_items + t / 4];
     const u64x4 rec = *reinterpret_cast<const u64x4*>(rops + item.op);
     const DDL_GLOBAL V* src = (const DDL_GLOBAL V*)rec.x;
     DDL_GLOBAL V* dst = (DDL_GLOBAL V*)rec.y;
     const int64_t n = int64_t(rec.z);
     const int64_t nv = n / VL;
     const int64_t shift = int64_t((rec.y % kRowBytes) / 16);
-    const int wave = threadIdx.x / 64;
-    const int64_t lane = threadIdx.x % 64;
-    for (int k = wave; k < kListRows; k += 4) {
+    if (whole) {
+        const int64_t first = (int64_t(item.row) + b % kListRows) * 64 - shift;
+        if (first <= nv) step_tile<T, REDUCE>(src, dst, n, nv, first, threadIdx.x);
+        return;
+    }
+    for (int k = t % 4; k < kListRows; k += 4) {
         const int64_t first = (int64_t(item.row) + k) * 64 - shift;
         if (first > nv) break;
-        step_tile<T, REDUCE>(src, dst, n, nv, first, lane);
+        step_tile<T, REDUCE>(src, dst, n, nv, first, threadIdx.x);
     }
 }
 
@@ -252,15 +262,26 @@ template <typename T>
 hipError_t launch_list_typed(const Step& step, const ResolvedOp* d_rops, const BlockDesc* d_descs,
                              hipStream_t stream) {
     if (step.desc_count == 0) return hipSuccess;
-    if (step.desc_count > 0x7FFFFFFFull) return hipErrorInvalidValue;
-    const dim3 grid(static_cast<unsigned>(step.desc_count), 1, 1);
-    if (step.kind == DDL_STEP_REDUCE)
-        hipLaunchKernelGGL((step_kernel_list<T, true>), grid, dim3(256), 0, stream, d_rops,
-                           d_descs + step.desc_first);
-    else
-        hipLaunchKernelGGL((step_kernel_list<T, false>), grid, dim3(256), 0, stream, d_rops,
-                           d_descs + step.desc_first);
-    return hipGetLastError();
+    const uint64_t whole_blocks = uint64_t(step.desc_whole) * kListRows;
+    const uint64_t blocks = whole_blocks + uint64_t(step.desc_count - step.desc_whole) * 4;
+    if (blocks > 0xFFFFFFFFull) return hipErrorInvalidValue;
+    // one launch holds at most 2^26 - 1 workgroups (64 threads each, below 2^32 threads)
+    const uint64_t per_launch = (uint64_t(1) << 26) - 1;
+    for (uint64_t start = 0; start < blocks; start += per_launch) {
+        const uint64_t now = blocks - start < per_launch ? blocks - start : per_launch;
+        const dim3 grid(static_cast<unsigned>(now), 1, 1);
+        if (step.kind == DDL_STEP_REDUCE)
+            hipLaunchKernelGGL((step_kernel_list<T, true>), grid, dim3(64), 0, stream, d_rops,
+                               d_descs + step.desc_first, unsigned(whole_blocks), unsigned(step.desc_whole),
+                               unsigned(start));
+        else
+            hipLaunchKernelGGL((step_kernel_list<T, false>), grid, dim3(64), 0, stream, d_rops,
+                               d_descs + step.desc_first, unsigned(whole_blocks), unsigned(step.desc_whole),
+                               unsigned(start));
+        const hipError_t err = hipGetLastError();
+        if (err != hipSuccess) return err;
+    }
+    return hipSuccess;
 }
 
 template <typename T>

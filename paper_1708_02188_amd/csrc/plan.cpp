@@ -77,7 +77,8 @@ void build_schedule(ddl_plan* plan) {
 
     auto emit = [&](int kind, int t, int phase) {
         const int d = plan->dims[t];
-        Step st{kind, t, 0, 0, plan->descs.size(), 0};
+        Step st{kind, t, 0, 0, plan->descs.size(), 0, 0};
+        std::vector<BlockDesc> ragged;
         const uint64_t per_elem = (kind == DDL_STEP_REDUCE ? 3u : 2u) * plan->elem_size;
         for (int s = 0; s < S; ++s) {
             for (int r = 0; r < P; ++r) {
@@ -98,15 +99,21 @@ void build_schedule(ddl_plan* plan) {
                 if (S > 1 && op.n > 0) {
                     // work list for the batched launch: spans of kListRows 1 KiB rows; one
                     // row more than the vectors need, because the tiling is shifted onto
-                    // absolute row boundaries at run time
+                    // absolute row boundaries at run time.  Whole spans go to the front of
+                    // the phase's slice, the ragged last span of each operation to its back.
                     const uint64_t rows = (op.n / G + 1 + 63 + 63) / 64;
                     const uint32_t index = static_cast<uint32_t>(plan->ops.size() % (size_t(S) * P));
-                    for (uint64_t row = 0; row < rows; row += kListRows)
-                        plan->descs.push_back(BlockDesc{index, static_cast<uint32_t>(row)});
+                    for (uint64_t row = 0; row < rows; row += kListRows) {
+                        const BlockDesc item{index, static_cast<uint32_t>(row)};
+                        if (row + kListRows <= rows) plan->descs.push_back(item);
+                        else ragged.push_back(item);
+                    }
                 }
                 plan->ops.push_back(op);
             }
         }
+        st.desc_whole = plan->descs.size() - st.desc_first;
+        plan->descs.insert(plan->descs.end(), ragged.begin(), ragged.end());
         st.desc_count = plan->descs.size() - st.desc_first;
         plan->bytes_total += st.bytes;
         plan->steps.push_back(st);

@@ -43,8 +43,9 @@ struct Step {
     int dim;            // 0-based box dimension whose rings run in this phase
     uint64_t max_n;     // longest operation of the phase (sizes the launch)
     uint64_t bytes;     // memory traffic of the phase
-    size_t desc_first;  // several-tensor plans: this phase's slice of the work list
-    size_t desc_count;
+    size_t desc_first;  // several-tensor plans: this phase's slice of the work list,
+    size_t desc_count;  // of which the first desc_whole items have all kListRows rows
+    size_t desc_whole;
 };
 
 // Tables of the step-fused allreduce.  Finest chunk c (owned by learner c) is summed over

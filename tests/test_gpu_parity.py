@@ -235,6 +235,32 @@ def test_capture_into_a_hip_graph_and_replay(dev):
             assert_bitwise(g, want[j], f"replay {replay} learner={j}")
 
 
+def test_buckets_on_two_streams(dev):
+    """A gradient buffer cut into two buckets, each with its own plan on its own stream
+    (how a framework would overlap the allreduce of early layers with later compute)."""
+    dims, P, count = [2, 4], 8, 400000
+    cut = 150000  # multiple of 4 elements: both buckets start 16-byte aligned
+    rng = np.random.default_rng(44)
+    V = wide_inputs(rng, P, count, D.DDL_F32)
+    bufs = upload(V, dev)
+    plans = [D.ddl_ring_plan(dims, P, cut), D.ddl_ring_plan(dims, P, count - cut)]
+    for p in plans:
+        D.ddl_plan_prepare(p)
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    torch.cuda.synchronize()
+    views = [[b[:cut] for b in bufs], [b[cut:] for b in bufs]]
+    for _ in range(2):  # two rounds back to back on each stream
+        for p, st, vw, n in zip(plans, streams, views, (cut, count - cut)):
+            D.ddl_allreduce_sim(vw, P, p, n, D.DDL_F32, st)
+    for st in streams:
+        st.synchronize()
+    want_a = O.allreduce_steps(O.allreduce_steps([v[:cut] for v in V], dims), dims)
+    want_b = O.allreduce_steps(O.allreduce_steps([v[cut:] for v in V], dims), dims)
+    for j, g in enumerate(download(bufs)):
+        assert_bitwise(g[:cut], want_a[j], f"bucket 0 learner={j}")
+        assert_bitwise(g[cut:], want_b[j], f"bucket 1 learner={j}")
+
+
 def test_buffers_as_aligned_views_of_one_allocation(dev):
     dims, count, P = [2, 2], 10007, 4
     stride = 10240  # elements; multiple of 4 -> 16-byte aligned views, non-overlapping
