@@ -235,6 +235,58 @@ def test_capture_into_a_hip_graph_and_replay(dev):
             assert_bitwise(g, want[j], f"replay {replay} learner={j}")
 
 
+@pytest.mark.parametrize("dtype", [D.DDL_F32, D.DDL_F16])
+def test_learners_at_different_alignments_within_a_kibibyte(dev, dtype):
+    """Learner buffers whose addresses differ modulo 1 KiB (16-byte steps): the kernels lay
+    their rows on the destination's 1 KiB boundaries, the source is then misaligned."""
+    dims, P = [2, 2, 2], 8
+    esz = 4 if dtype == D.DDL_F32 else 2
+    G = 16 // esz
+    count = 70001
+    starts = [j * 80000 + (j * 7 % 64) * G for j in range(P)]   # element offsets, odd multiples of 16 bytes
+    rng = np.random.default_rng(52)
+    V = wide_inputs(rng, P, count, dtype)
+    slab = torch.zeros(P * 80000 + 1024, dtype=torch.float32 if esz == 4 else torch.float16, device=dev)
+    bufs = [slab[s0:s0 + count] for s0 in starts]
+    assert len({b.data_ptr() % 1024 for b in bufs}) > 4
+    for b, v in zip(bufs, V):
+        b.copy_(torch.from_numpy(v))
+    plan = D.ddl_ring_plan(dims, P, count, dtype)
+    D.ddl_allreduce_sim(bufs, P, plan, count, dtype)
+    want = O.allreduce_steps(V, dims)
+    for j, g in enumerate(download(bufs)):
+        assert_bitwise(g, want[j], f"misaligned learner={j}")
+    # the fused path on the same layout
+    for b, v in zip(bufs, V):
+        b.copy_(torch.from_numpy(v))
+    D.ddl_allreduce_fused_sim(bufs, P, plan, count, dtype)
+    for j, g in enumerate(download(bufs)):
+        assert_bitwise(g, want[j], f"misaligned fused learner={j}")
+    # nothing outside the learners' ranges was written
+    torch.cuda.synchronize()
+    mask = torch.ones_like(slab, dtype=torch.bool)
+    for s0 in starts:
+        mask[s0:s0 + count] = False
+    assert not slab[mask].any()
+
+
+def test_counts_around_row_and_tile_edges(dev):
+    """Lengths that end just before, on and after 1 KiB rows, for a 16-bit and a 64-bit type."""
+    for dtype, npdt in ((D.DDL_F64, np.float64), (D.DDL_BF16, np.uint16), (D.DDL_F32, np.float32)):
+        vl = 16 // np.dtype(npdt).itemsize
+        for count in (64 * vl - 1, 64 * vl, 64 * vl + 1, 2 * 64 * vl * 3 + vl - 1, 3 * 64 * vl * 2 + 2 * vl + 1):
+            dims, P = [3, 2], 6
+            rng = np.random.default_rng(count)
+            V = wide_inputs(rng, P, count, dtype)
+            bufs = upload(V, dev)
+            plan = D.ddl_ring_plan(dims, P, count, dtype)
+            D.ddl_allreduce_sim(bufs, P, plan, count, dtype)
+            add = O.bf16_add if dtype == D.DDL_BF16 else None
+            want = O.allreduce_steps(V, dims, add=add)
+            for j, g in enumerate(download(bufs, npdt)):
+                assert_bitwise(g, want[j], f"dtype={dtype} count={count} learner={j}")
+
+
 def test_buckets_on_two_streams(dev):
     """A gradient buffer cut into two buckets, each with its own plan on its own stream
     (how a framework would overlap the allreduce of early layers with later compute)."""
