@@ -410,6 +410,42 @@ __global__ __launch_bounds__(64) void fused_kernel(const uint64_t* ptrs_, const 
     }
 }
 
+// Distribution pass of the two-pass form: workgroup (tile, destination group, chunk) reads
+// one row of the chunk from its owner and stores it to the learners of its group.
+// Measured: the fewer groups the better (a group per destination re-reads the row P-1
+// times and, although those reads hit in cache, they still cross the fabric); the default
+// puts all destinations into one group.
+#ifndef DDL_GATHER_GROUP
+#define DDL_GATHER_GROUP DDL_FUSED_MAX_LEARNERS
+#endif
+template <typename T>
+__global__ __launch_bounds__(64) void fused_gather_kernel(const uint64_t* ptrs_, const uint64_t* chunk_n_,
+                                                          int P, int padded, unsigned tile_stride) {
+    typedef typename Elem<T>::V V;
+    typedef typename Elem<T>::S S;
+    constexpr int64_t VL = 16 / sizeof(S);
+    const DDL_CONST uint64_t* row = (const DDL_CONST uint64_t*)ptrs_ + size_t(blockIdx.z) * padded;
+    const int64_t n = int64_t(((const DDL_CONST uint64_t*)chunk_n_)[blockIdx.z]);
+    const int64_t nv = n / VL;
+    const uint64_t src_addr = row[P - 1];
+    const int64_t shift = int64_t((src_addr % kRowBytes) / 16);
+    const int j0 = blockIdx.y * DDL_GATHER_GROUP;
+    const int j1 = j0 + DDL_GATHER_GROUP < P - 1 ? j0 + DDL_GATHER_GROUP : P - 1;
+    const int64_t tid = threadIdx.x;
+    for (int64_t first = int64_t(blockIdx.x) * 64 - shift; first <= nv; first += int64_t(tile_stride) * 64) {
+        const int64_t v = first + tid;
+        if (v >= 0 && v < nv) {
+            const V x = stream_load((const DDL_GLOBAL V*)src_addr + v);
+            for (int j = j0; j < j1; ++j) stream_store((DDL_GLOBAL V*)row[j] + v, x);
+        } else if (v == nv) {
+            for (int64_t e = nv * VL; e < n; ++e) {
+                const S x = ((const DDL_GLOBAL S*)src_addr)[e];
+                for (int j = j0; j < j1; ++j) ((DDL_GLOBAL S*)row[j])[e] = x;
+            }
+        }
+    }
+}
+
 template <typename T>
 hipError_t launch_fused_typed(const ddl_plan& plan, const DeviceTables& t, int padded, int levels,
                               uint64_t max_chunk, int mode, hipStream_t stream) {
@@ -424,9 +460,14 @@ hipError_t launch_fused_typed(const ddl_plan& plan, const DeviceTables& t, int p
     else if (mode == FUSED_REDUCE)
         hipLaunchKernelGGL((fused_kernel<T, FUSED_REDUCE>), grid, dim3(64), 0, stream, t.fused_ptrs,
                            t.fused_ctl, t.fused_n, plan.P, padded, levels, grid.x);
-    else
-        hipLaunchKernelGGL((fused_kernel<T, FUSED_GATHER>), grid, dim3(64), 0, stream, t.fused_ptrs,
-                           t.fused_ctl, t.fused_n, plan.P, padded, levels, grid.x);
+    else {
+        const unsigned groups = static_cast<unsigned>((plan.P - 1 + DDL_GATHER_GROUP - 1) / DDL_GATHER_GROUP);
+        const uint64_t max_x3 = ((uint64_t(1) << 32) / 64 - 1) / (uint64_t(plan.P) * groups);
+        const unsigned x = static_cast<unsigned>(tiles > max_x3 ? max_x3 : tiles);
+        const dim3 grid3(x ? x : 1, groups, static_cast<unsigned>(plan.P));
+        hipLaunchKernelGGL((fused_gather_kernel<T>), grid3, dim3(64), 0, stream, t.fused_ptrs, t.fused_n,
+                           plan.P, padded, grid3.x);
+    }
     return hipGetLastError();
 }
 
