@@ -21,6 +21,48 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 
 
+def box_sweep(torch, D, dev, P=256, iters=30):
+    """Sec. 4.3: a ring's time has a latency term per phase, so for many learners a box with
+    fewer phases wins although it moves the same bytes.  On one GPU the latency of a phase
+    is a kernel-launch boundary.  Times every box on three buffer sizes, fits
+    T = phases * L + bytes / B by least squares and asks ddl_choose_dims with the fit."""
+    import numpy as np
+
+    boxes = [[256], [16, 16], [4, 64], [64, 4], [4, 8, 8], [4, 4, 4, 4], [2] * 8]
+    stream = torch.cuda.current_stream()
+    rows = []
+    for count in (4096, 65536, 1 << 20):
+        bufs = [torch.zeros(count, dtype=torch.float32, device=dev) for _ in range(P)]
+        for dims in boxes:
+            plan = D.ddl_ring_plan(dims, P, count)
+            D.ddl_plan_prepare(plan)
+            for _ in range(3):
+                D.ddl_allreduce_sim(bufs, P, plan, count, D.DDL_F32, stream)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(iters):
+                D.ddl_allreduce_sim(bufs, P, plan, count, D.DDL_F32, stream)
+            torch.cuda.synchronize()
+            us = (time.perf_counter() - t0) / iters * 1e6
+            rows.append({"count": count, "dims": dims, "phases": D.ddl_plan_num_steps(plan),
+                         "bytes": D.ddl_plan_bytes_moved(plan), "us": round(us, 1)})
+        del bufs
+    A = np.array([[r["phases"], r["bytes"]] for r in rows], dtype=np.float64)
+    y = np.array([r["us"] * 1e-6 for r in rows])
+    (L, invB), *_ = np.linalg.lstsq(A, y, rcond=None)
+    picks = {}
+    for count in (4096, 65536, 1 << 20):
+        dims, t = D.ddl_choose_dims(P, 4 * count, [1.0 / invB / 2.5] * 8, [float(L)] * 8)
+        best = min((r for r in rows if r["count"] == count), key=lambda r: r["us"])
+        picks[str(count)] = {"chooser": [d for d in dims if d > 1], "modelled_us": round(t * 1e6, 1),
+                             "fastest_measured": best["dims"], "fastest_us": best["us"]}
+    print(json.dumps({"mode": "box_sweep", "P": P, "iters": iters, "results": rows,
+                      "fit": {"latency_per_phase_us": round(L * 1e6, 3), "bandwidth_GBs": round(1e-9 / invB, 1),
+                              "note": "the chooser's per-link bandwidth is the fitted rate / 2.5: the model "
+                                      "counts 4 bytes per element and transfer, the kernels move 12 or 8"},
+                      "chooser": picks}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -37,6 +79,9 @@ def main():
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="also run one plain device-to-device copy of this many MiB (a dispatch of "
                          "known size, to scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
+    ap.add_argument("--box-sweep", action="store_true",
+                    help="instead of the benchmark line: time P=256 learners arranged as different boxes "
+                         "on small buffers (the latency regime the multi-dimensional ring is for)")
     args = ap.parse_args()
 
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -53,6 +98,19 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(3)
     dev = torch.device("cuda:0")
+    props = torch.cuda.get_device_properties(0)
+    try:
+        mem_khz, bus_bits = D.ddl_device_memory_info()
+    except D.DdlError:
+        mem_khz, bus_bits = None, None
+    device_info = {"name": props.name, "memory_clock_khz": mem_khz, "memory_bus_bits": bus_bits,
+                   # double data rate: 2 transfers per clock
+                   "clock_x_bus_GBs": (2 * mem_khz * 1e3 * bus_bits / 8 / 1e9) if mem_khz and bus_bits else None,
+                   "peak_used_GBs": HBM_PEAK_GBS, "hbm_bytes": props.total_memory,
+                   "compute_units": props.multi_processor_count}
+    if args.box_sweep:
+        box_sweep(torch, D, dev)
+        return
     cfg = I.CONFIGS[args.config - 1]
     P, dims, count, dist, seed = cfg["P"], cfg["dims"], cfg["count"], cfg["dist"], cfg["seed"]
     K, W = args.steps, args.warmup
@@ -238,6 +296,7 @@ def main():
                    "input_sets": n_sets, "bus_GBs_per_learner": per_learner_gbs * 2 * (P - 1) / P},
         "hbm_GBs": hbm_gbs, "hbm_frac_of_peak": hbm_gbs / HBM_PEAK_GBS,
         "learners_identical": bool(same),
+        "device": device_info,
         "roofline": roofline,
         "fused_variant": fused,
         "per_tensor_variant": per_tensor,

@@ -241,6 +241,10 @@ double ddl_plan_model_time(const ddl_plan_t* plan, const double* bw, const doubl
 ddl_status_t ddl_choose_dims(int P, size_t bytes, int m, const double* bw, const double* lat,
                              const int* max_dim, int* dims_out, double* time_out);
 
+/* Memory clock (kHz) and bus width (bits) of the current device as the HIP runtime reports
+ * them, for stating the bandwidth peak next to a measurement.  DDL_ERR_HIP without a device. */
+ddl_status_t ddl_device_memory_info(int* clock_khz, int* bus_bits);
+
 /* Static, human-readable name of a status code. */
 const char* ddl_status_string(ddl_status_t status);
 

@@ -52,6 +52,7 @@ def _load():
         "ddl_choose_dims": (i, [i, sz, i, ctypes.POINTER(ctypes.c_double),
                                 ctypes.POINTER(ctypes.c_double), pi, pi,
                                 ctypes.POINTER(ctypes.c_double)]),
+        "ddl_device_memory_info": (i, [pi, pi]),
         "ddl_status_string": (ctypes.c_char_p, [i]),
     }
     for name, (res, args) in sigs.items():
@@ -243,3 +244,10 @@ def ddl_choose_dims(P, nbytes, bw, lat, max_dim=None):
                                 (ctypes.c_double * max(m, 1))(*lat), caps, dims, ctypes.byref(t)),
            "ddl_choose_dims")
     return list(dims)[:m], t.value
+
+
+def ddl_device_memory_info():
+    """Returns (memory clock in kHz, bus width in bits) of the current device."""
+    clock, bus = ctypes.c_int(0), ctypes.c_int(0)
+    _check(_lib.ddl_device_memory_info(ctypes.byref(clock), ctypes.byref(bus)), "ddl_device_memory_info")
+    return clock.value, bus.value

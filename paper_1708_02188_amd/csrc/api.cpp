@@ -445,6 +445,17 @@ ddl_status_t ddl_choose_dims(int P, size_t bytes, int m, const double* bw, const
     return ddl::choose_dims(P, double(bytes), m, bw, lat, max_dim, dims_out, time_out);
 }
 
+ddl_status_t ddl_device_memory_info(int* clock_khz, int* bus_bits) {
+    int device = -1, clock = 0, bus = 0;
+    if (hipGetDevice(&device) != hipSuccess ||
+        hipDeviceGetAttribute(&clock, hipDeviceAttributeMemoryClockRate, device) != hipSuccess ||
+        hipDeviceGetAttribute(&bus, hipDeviceAttributeMemoryBusWidth, device) != hipSuccess)
+        return DDL_ERR_HIP;
+    if (clock_khz) *clock_khz = clock;
+    if (bus_bits) *bus_bits = bus;
+    return DDL_OK;
+}
+
 const char* ddl_status_string(ddl_status_t status) {
     switch (status) {
         case DDL_OK: return "ok";

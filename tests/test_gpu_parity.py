@@ -354,6 +354,57 @@ def test_more_learners_than_the_kernarg_table_holds(dev):
 
 
 # ---------------------------------------------------------------------------------------
+# seeded random sweep over boxes, lengths, element types and entry points
+# ---------------------------------------------------------------------------------------
+def random_box(rng, max_P=48):
+    dims = []
+    P = 1
+    for _ in range(int(rng.integers(1, 5))):
+        d = int(rng.integers(1, 7))
+        if P * d > max_P:
+            break
+        dims.append(d)
+        P *= d
+    return dims or [1]
+
+
+def test_random_sweep_against_oracle(dev):
+    rng = np.random.default_rng(20260101)
+    dtypes = [D.DDL_F32, D.DDL_F64, D.DDL_I32, D.DDL_F16, D.DDL_BF16]
+    for case in range(60):
+        dims = random_box(rng)
+        P = prod(dims)
+        dtype = dtypes[int(rng.integers(0, len(dtypes)))]
+        count = int(rng.choice([0, 1, 3, 17, 255, 1024, 4097, 30011, 200003]) + rng.integers(0, 9))
+        entry = ["allreduce", "fused", "tensors"][int(rng.integers(0, 3))]
+        levels = sum(d > 1 for d in dims)
+        if entry == "fused" and levels > 4:
+            entry = "allreduce"
+        say(f"case {case}: dims={dims} dtype={dtype} count={count} entry={entry}")
+        V = wide_inputs(rng, P, count, dtype)
+        add = O.bf16_add if dtype == D.DDL_BF16 else None
+        bufs = upload(V, dev)
+        with np.errstate(over="ignore"):
+            if entry == "tensors":
+                G = 16 // V[0].dtype.itemsize
+                cuts = sorted(set(int(x) // G * G for x in rng.integers(0, count + 1, 5)) | {0})
+                segments = [(a, int(rng.integers(0, b - a + 1))) for a, b in zip(cuts, cuts[1:] + [count])]
+                plan = D.ddl_ring_plan_tensors(dims, P, [o for o, _ in segments], [n for _, n in segments],
+                                               count, dtype)
+                D.ddl_allreduce_sim(bufs, P, plan, count, dtype)
+                want = O.allreduce_tensors(V, dims, segments, add=add)
+            else:
+                plan = D.ddl_ring_plan(dims, P, count, dtype)
+                if entry == "fused":
+                    D.ddl_allreduce_fused_sim(bufs, P, plan, count, dtype)
+                else:
+                    D.ddl_allreduce_sim(bufs, P, plan, count, dtype)
+                want = O.allreduce_steps(V, dims, add=add)
+        for j, g in enumerate(download(bufs, V[0].dtype)):
+            assert_bitwise(g, want[j], f"case {case} learner={j}")
+
+
+# ---------------------------------------------------------------------------------------
 # several tensors per buffer, each reduced on its own, transfers batched per phase
 # ---------------------------------------------------------------------------------------
 TENSOR_CASES = [

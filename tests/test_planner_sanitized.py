@@ -1,0 +1,85 @@
+"""The host-side planner compiled with AddressSanitizer and UBSan (host code only, no HIP)
+and driven through a sweep of boxes, lengths and tensor lists."""
+import os
+import shutil
+import subprocess
+import sys
+
+import pytest
+
+from conftest import ROOT
+
+DRIVER = r'''
+#include <cstdio>
+#include <cstdlib>
+#include <vector>
+#include "plan.h"
+
+static void one(const std::vector<int>& dims, uint64_t count, ddl_dtype_t dtype,
+                const std::vector<uint64_t>& off, const std::vector<uint64_t>& cnt) {
+    int P = 1;
+    for (int d : dims) P *= d;
+    if (ddl::validate_dims(dims.data(), (int)dims.size(), P) != DDL_OK) std::abort();
+    ddl_plan plan;
+    plan.dims = dims;
+    plan.P = P;
+    plan.count = count;
+    plan.dtype = dtype;
+    plan.elem_size = ddl::dtype_size(dtype);
+    plan.seg_off = off;
+    plan.seg_count = cnt;
+    ddl::build_schedule(&plan);
+    size_t steps = 0;
+    for (int d : dims) steps += 2 * (d - 1);
+    if (plan.steps.size() != steps) std::abort();
+    if (plan.ops.size() != steps * off.size() * (size_t)P) std::abort();
+    for (const ddl::Op& op : plan.ops)
+        if (op.off + op.n > count || op.src < 0 || op.src >= P || op.dst < 0 || op.dst >= P) std::abort();
+    for (const ddl::BlockDesc& d : plan.descs)
+        if (d.op >= off.size() * (size_t)P) std::abort();
+    int levels = 0;
+    for (int d : dims) levels += d > 1;
+    if (P <= 64 && levels >= 1) {
+        std::vector<uint32_t> seq, ctl;
+        int padded = 0;
+        if (ddl::build_fused_order(plan, &seq, &ctl, &padded) != levels) std::abort();
+        for (uint32_t r : seq)
+            if (r >= (uint32_t)P) std::abort();
+    }
+}
+
+int main() {
+    const std::vector<std::vector<int>> boxes = {{1}, {2}, {5}, {4, 4}, {3, 1, 2}, {2, 2, 2, 2}, {4, 8, 8}, {7, 3}, {1, 1}};
+    const uint64_t counts[] = {0, 1, 4, 5, 37, 1000, 65537, 25557032};
+    const ddl_dtype_t types[] = {DDL_F32, DDL_F64, DDL_F16};
+    for (const auto& dims : boxes)
+        for (uint64_t c : counts)
+            for (ddl_dtype_t t : types) {
+                if (c > 100000 && dims.size() > 3) continue;
+                one(dims, c, t, {0}, {c});
+                if (c >= 64) one(dims, c, t, {0, 16, 48}, {9, 32, c - 48});
+            }
+    int dims3[3];
+    double bw[3] = {2e10, 1e10, 9.5e9}, lat[3] = {1e-5, 1e-5, 1e-5}, time = 0;
+    int caps[3] = {4, 16, 0};
+    if (ddl::choose_dims(256, 3.5e8, 3, bw, lat, caps, dims3, &time) != DDL_OK) std::abort();
+    std::puts("planner sweep ok");
+    return 0;
+}
+'''
+
+
+@pytest.mark.skipif(shutil.which("g++") is None, reason="needs g++")
+def test_planner_under_asan_and_ubsan(tmp_path):
+    csrc = os.path.join(ROOT, "paper_1708_02188_amd", "csrc")
+    drv = tmp_path / "driver.cpp"
+    drv.write_text(DRIVER)
+    exe = tmp_path / "planner_asan"
+    cmd = ["g++", "-std=c++17", "-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=all",
+           "-static-libasan", "-static-libubsan",
+           "-I", csrc, str(drv), os.path.join(csrc, "plan.cpp"), "-o", str(exe), "-pthread"]
+    subprocess.run(cmd, check=True)
+    run = subprocess.run([str(exe)], capture_output=True, text=True, timeout=300)
+    sys.stdout.write(run.stdout)
+    sys.stderr.write(run.stderr[-2000:])
+    assert run.returncode == 0 and "planner sweep ok" in run.stdout
