@@ -16,7 +16,19 @@ def library_path():
     return os.environ.get("DDLSIM_LIBRARY") or os.path.join(_PKG, "libddlsim.so")
 
 
+def _one_hip_runtime():
+    """PyTorch wheels bundle their own libamdhip64 under the same SONAME as the system's; the
+    first one loaded serves the whole process.  If this library came first, torch would run on
+    a runtime it was not built for (its launches then fail), so torch, when present, is
+    imported before the library is opened."""
+    try:
+        import torch  # noqa: F401
+    except ImportError:
+        pass
+
+
 def _load():
+    _one_hip_runtime()
     path = library_path()
     if not os.path.exists(path):
         raise ImportError(

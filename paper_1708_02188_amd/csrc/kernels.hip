@@ -6,6 +6,8 @@
 //                                                               i.e. the paper's assignment)
 //   resolve_ops     : per call, turns the plan's (learner, offset) operations into absolute
 //                     (src address, dst address, length) records for the caller's buffers
+//   step_kernel_list: the same two phase operations for plans over several tensors
+//   fused_kernel, fused_gather_kernel: the step-fused allreduce (further down)
 //
 // The two phase kernels stream through HBM once: 12 resp. 8 bytes of traffic per fp32
 // element and one add, so the bound is memory bandwidth.  No LDS (every element is touched
@@ -17,8 +19,7 @@
 // order, not from persistent or deeply unrolled loops: the set of rows in flight then
 // stays a narrow window that slides through memory.  A workgroup that small lives only a
 // few memory latencies, so its prologue must be short: the operation record is one
-// 32-byte scalar load from a table of absolute addresses (written by resolve_ops), and
-// the table pointer is a preloaded kernel argument.
+// 32-byte scalar load from a table of absolute addresses (written by resolve_ops).
 //
 // Grid: blockIdx.y = operation (sending learner), blockIdx.x strides over that
 // operation's tiles.  Consecutive workgroups are handed to the 8 XCDs round-robin, so
@@ -47,67 +48,49 @@
 namespace ddl {
 namespace {
 
-// Element traits: the 16-byte vector a lane moves, and the sum of two vectors / elements.
+// Element traits: the scalar S as stored, the 16-byte vector V a lane moves, and the sum of
+// two of either (X = S or V), formed in the element type with one rounding per element.
 template <typename T> struct Elem;
 template <> struct Elem<float> {
     typedef float S;
     typedef float V __attribute__((ext_vector_type(4)));
-    static __device__ __forceinline__ V add(V a, V b) { return a + b; }
-    static __device__ __forceinline__ S add1(S a, S b) { return a + b; }
     template <typename X> static __device__ __forceinline__ X sum(X a, X b) { return a + b; }
 };
 template <> struct Elem<double> {
     typedef double S;
     typedef double V __attribute__((ext_vector_type(2)));
-    static __device__ __forceinline__ V add(V a, V b) { return a + b; }
-    static __device__ __forceinline__ S add1(S a, S b) { return a + b; }
     template <typename X> static __device__ __forceinline__ X sum(X a, X b) { return a + b; }
 };
 // 32-bit integers are summed as unsigned: wrap-around, the same bits as two's complement
 template <> struct Elem<unsigned> {
     typedef unsigned S;
     typedef unsigned V __attribute__((ext_vector_type(4)));
-    static __device__ __forceinline__ V add(V a, V b) { return a + b; }
-    static __device__ __forceinline__ S add1(S a, S b) { return a + b; }
     template <typename X> static __device__ __forceinline__ X sum(X a, X b) { return a + b; }
 };
 template <> struct Elem<_Float16> {
     typedef _Float16 S;
     typedef _Float16 V __attribute__((ext_vector_type(8)));
-    static __device__ __forceinline__ V add(V a, V b) { return a + b; }
-    static __device__ __forceinline__ S add1(S a, S b) { return a + b; }
     template <typename X> static __device__ __forceinline__ X sum(X a, X b) { return a + b; }
 };
 // bfloat16 travels as its 16 raw bits; widened to binary32 (exact), added there, and
 // rounded back to the nearest bfloat16, ties to even.
-struct bf16_bits {
-    unsigned short u;
-};
+struct bf16_bits {};
 template <> struct Elem<bf16_bits> {
     typedef unsigned short S;
     typedef unsigned short V __attribute__((ext_vector_type(8)));
-    static __device__ __forceinline__ S add1(S a, S b) {
+    static __device__ __forceinline__ S sum(S a, S b) {
         const float f = __uint_as_float(unsigned(a) << 16) + __uint_as_float(unsigned(b) << 16);
         const unsigned w = __float_as_uint(f);
         if ((w & 0x7FFFFFFFu) > 0x7F800000u) return S((w >> 16) | 0x0040u);  // NaN stays NaN
         return S((w + 0x7FFFu + ((w >> 16) & 1u)) >> 16);
     }
-    static __device__ __forceinline__ V add(V a, V b) {
+    static __device__ __forceinline__ V sum(V a, V b) {
         V r;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) r[i] = add1(a[i], b[i]);
+        for (int i = 0; i < 8; ++i) r[i] = sum(S(a[i]), S(b[i]));
         return r;
     }
-    template <typename X> static __device__ __forceinline__ X sum(X a, X b);
 };
-template <> __device__ __forceinline__ unsigned short Elem<bf16_bits>::sum<unsigned short>(unsigned short a,
-                                                                                          unsigned short b) {
-    return add1(a, b);
-}
-template <> __device__ __forceinline__ Elem<bf16_bits>::V Elem<bf16_bits>::sum<Elem<bf16_bits>::V>(
-    Elem<bf16_bits>::V a, Elem<bf16_bits>::V b) {
-    return add(a, b);
-}
 
 // Pointers are tagged as global memory so the loads and stores are global_* rather than
 // flat_* instructions (no aperture check, no LDS counter involvement).
@@ -176,7 +159,7 @@ __device__ __forceinline__ void step_tile(const DDL_GLOBAL typename Elem<T>::V* 
 #pragma unroll
             for (int u = 0; u < DDL_UNROLL; ++u) b[u] = stream_load(d + u * DDL_THREADS);
 #pragma unroll
-            for (int u = 0; u < DDL_UNROLL; ++u) a[u] = Elem<T>::add(b[u], a[u]);
+            for (int u = 0; u < DDL_UNROLL; ++u) a[u] = Elem<T>::sum(b[u], a[u]);
         }
 #pragma unroll
         for (int u = 0; u < DDL_UNROLL; ++u) stream_store(d + u * DDL_THREADS, a[u]);
@@ -187,7 +170,7 @@ __device__ __forceinline__ void step_tile(const DDL_GLOBAL typename Elem<T>::V* 
             const int64_t v = first + u * DDL_THREADS + tid;
             if (v >= 0 && v < nv) {
                 V a = src[v];
-                if (REDUCE) a = Elem<T>::add(dst[v], a);
+                if (REDUCE) a = Elem<T>::sum(dst[v], a);
                 dst[v] = a;
             } else if (v == nv) {
                 // the buffer's last, short vector: element by element
@@ -195,7 +178,7 @@ __device__ __forceinline__ void step_tile(const DDL_GLOBAL typename Elem<T>::V* 
                 DDL_GLOBAL S* de = (DDL_GLOBAL S*)(dst + nv);
                 for (int64_t e = 0; e < n - nv * VL; ++e) {
                     S a = se[e];
-                    if (REDUCE) a = Elem<T>::add1(de[e], a);
+                    if (REDUCE) a = Elem<T>::sum(de[e], a);
                     de[e] = a;
                 }
             }
@@ -330,57 +313,51 @@ __global__ __launch_bounds__(256) void fused_resolve(const PtrTable table, void*
 template <typename T, typename X>
 __device__ __forceinline__ void fused_feed(X (&acc)[DDL_FUSED_MAX_LEVELS], X v, uint32_t word, int levels) {
     if (word & 1u) acc[0] = v;
-    else acc[0] = Elem<T>::template sum<X>(acc[0], v);
+    else acc[0] = Elem<T>::sum(acc[0], v);
     if (!(word & 0x100u)) return;  // the ring of level 0 is not complete yet
     v = acc[0];
 #pragma unroll
     for (int t = 1; t < DDL_FUSED_MAX_LEVELS; ++t) {
         if (t >= levels) return;
         if ((word >> t) & 1u) acc[t] = v;
-        else acc[t] = Elem<T>::template sum<X>(acc[t], v);
+        else acc[t] = Elem<T>::sum(acc[t], v);
         if (!((word >> (8 + t)) & 1u)) return;
         v = acc[t];
     }
 }
 
-// What one pass of the fused kernel does at every place of a finest chunk.
-enum { FUSED_ALL = 0,      // fold all learners, store the result to all of them
-       FUSED_REDUCE = 1,   // fold all learners, store the result to the chunk's owner only
-       FUSED_GATHER = 2 }; // copy the owner's value to every other learner
+// What one pass of the fused kernel stores at every place of a finest chunk.
+enum { FUSED_ALL = 0,      // the result to all learners (single-pass form)
+       FUSED_REDUCE = 1 }; // the result to the chunk's owner only (first pass of two)
 
-// All P learners' values at one place (a 16-byte vector X = V, or one element X = S).
-// The chunk's owner is the last learner of the summation order (the partial sum travels
-// once round every ring and ends at the owner's position).
+// All P learners' values at one place (a 16-byte vector X = V, or one element X = S): fold
+// them in schedule order and store the result.  The chunk's owner is the last learner of
+// the summation order (the partial sum travels once round every ring and ends at the
+// owner's position).
 template <typename T, typename X, int MODE>
 __device__ __forceinline__ void fused_place(const DDL_CONST uint64_t* row, const DDL_CONST uint32_t* ctl,
                                             int P, int padded, int levels, uint64_t byte_off) {
-    X result;
-    if (MODE == FUSED_GATHER) {
-        result = stream_load((const DDL_GLOBAL X*)(row[P - 1] + byte_off));
-    } else {
-        X acc[DDL_FUSED_MAX_LEVELS];
-        for (int i0 = 0; i0 < padded; i0 += kFusedBatch) {
-            X x[kFusedBatch];
+    X acc[DDL_FUSED_MAX_LEVELS];
+    for (int i0 = 0; i0 < padded; i0 += kFusedBatch) {
+        X x[kFusedBatch];
 #pragma unroll
-            for (int j = 0; j < kFusedBatch; ++j)
-                x[j] = stream_load((const DDL_GLOBAL X*)(row[i0 + j] + byte_off));
+        for (int j = 0; j < kFusedBatch; ++j)
+            x[j] = stream_load((const DDL_GLOBAL X*)(row[i0 + j] + byte_off));
 #pragma unroll
-            for (int j = 0; j < kFusedBatch; ++j) {
-                const uint32_t word = ctl[i0 + j];
-                if (word & kFusedValid) fused_feed<T, X>(acc, x[j], word, levels);
-            }
+        for (int j = 0; j < kFusedBatch; ++j) {
+            const uint32_t word = ctl[i0 + j];
+            if (word & kFusedValid) fused_feed<T, X>(acc, x[j], word, levels);
         }
-        result = acc[levels - 1];
     }
+    const X result = acc[levels - 1];
     if (MODE == FUSED_REDUCE) {
         stream_store((DDL_GLOBAL X*)(row[P - 1] + byte_off), result);
         return;
     }
-    const int stores = MODE == FUSED_GATHER ? P - 1 : P;
-    for (int i0 = 0; i0 < stores; i0 += kFusedBatch) {
+    for (int i0 = 0; i0 < P; i0 += kFusedBatch) {
 #pragma unroll
         for (int j = 0; j < kFusedBatch; ++j)
-            if (i0 + j < stores) stream_store((DDL_GLOBAL X*)(row[i0 + j] + byte_off), result);
+            if (i0 + j < P) stream_store((DDL_GLOBAL X*)(row[i0 + j] + byte_off), result);
     }
 }
 

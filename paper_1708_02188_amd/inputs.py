@@ -24,6 +24,10 @@ def library_path():
 
 
 def _load():
+    try:
+        import torch  # noqa: F401  (its bundled HIP runtime must be the process's only one)
+    except ImportError:
+        pass
     path = library_path()
     if not os.path.exists(path):
         raise ImportError(f"{path} is missing: build it with `python -m paper_1708_02188_amd.build`")

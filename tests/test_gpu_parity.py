@@ -63,6 +63,26 @@ def assert_bitwise(got, want, what):
                              f"got {got[diff[:5]]} want {want[diff[:5]]}")
 
 
+def test_library_before_torch_in_a_fresh_process():
+    """Import order must not matter: the binding makes sure one HIP runtime serves both."""
+    import subprocess
+    code = (
+        "import paper_1708_02188_amd.binding as B, paper_1708_02188_amd.inputs as I\n"
+        "import torch\n"
+        "P, n = 4, 5000\n"
+        "bufs = [torch.empty(n, dtype=torch.float32, device='cuda') for _ in range(P)]\n"
+        "for j, b in enumerate(bufs): I.fill_device(b, 7, j, 'int8')\n"
+        "plan = B.ddl_ring_plan([2, 2], P, n)\n"
+        "B.ddl_allreduce_sim(bufs, P, plan, n)\n"
+        "torch.cuda.synchronize()\n"
+        "want = sum(I.fill_host(n, 7, j, 'int8') for j in range(P))\n"
+        "assert all((b.cpu().numpy() == want).all() for b in bufs)\n"
+        "print('order ok')\n")
+    from conftest import ROOT
+    run = subprocess.run([sys.executable, "-c", code], cwd=ROOT, capture_output=True, text=True, timeout=240)
+    assert run.returncode == 0 and "order ok" in run.stdout, run.stderr[-2000:]
+
+
 # ---------------------------------------------------------------------------------------
 # the generator: device fill == host fill
 # ---------------------------------------------------------------------------------------
