@@ -98,8 +98,11 @@ ddl_plan_t* ddl_ring_plan_tensors(const int* dims, int m, int P, const size_t* t
 void ddl_plan_free(ddl_plan_t* plan);
 
 /*
- * Copy the plan's step tables into device memory of the current device now, instead of
- * at the first ddl_*_sim call that uses them (which otherwise allocates once).
+ * Create the plan's device tables on the current device now (those of the step-fused path
+ * included, where it serves the plan), instead of at the first ddl_*_sim call that needs
+ * them, which otherwise allocates once.  Call it before capturing ddl_*_sim calls into a
+ * HIP graph: under capture nothing may allocate.  Capture needs P <= 256 as well (beyond
+ * that every call stages the pointer array with a host-to-device copy).
  */
 ddl_status_t ddl_plan_prepare(const ddl_plan_t* plan);
 

@@ -249,9 +249,21 @@ void ddl_plan_free(ddl_plan_t* plan) {
     delete plan;
 }
 
+namespace {
+
+// Whether ddl_allreduce_fused_sim serves this plan.
+bool fused_supported(const ddl_plan* plan) {
+    int levels = 0;
+    for (int d : plan->dims) levels += d > 1;
+    return plan->P <= DDL_FUSED_MAX_LEARNERS && levels <= DDL_FUSED_MAX_LEVELS && plan->seg_off.size() == 1;
+}
+
+}  // namespace
+
 ddl_status_t ddl_plan_prepare(const ddl_plan_t* plan) {
     if (plan == nullptr) return DDL_ERR_ARG;
     DeviceTables t;
+    if (plan->P > 1 && plan->count > 0 && fused_supported(plan)) return fused_tables(plan, &t);
     return device_tables(plan, &t);
 }
 
@@ -278,11 +290,8 @@ ddl_status_t ddl_allreduce_fused_sim(void** bufs, int P, const ddl_plan_t* plan,
                                      ddl_dtype_t dtype, void* stream_v) {
     ddl_status_t st = check_call(bufs, P, plan, count, dtype);
     if (st != DDL_OK) return st;
-    int levels = 0;
-    for (int d : plan->dims) levels += d > 1;
-    if (P > DDL_FUSED_MAX_LEARNERS || levels > DDL_FUSED_MAX_LEVELS || plan->seg_off.size() != 1)
-        return DDL_ERR_UNSUPPORTED;
-    if (count == 0 || levels == 0) return DDL_OK;
+    if (!fused_supported(plan)) return DDL_ERR_UNSUPPORTED;
+    if (count == 0 || P == 1) return DDL_OK;
     hipStream_t stream = static_cast<hipStream_t>(stream_v);
     DeviceTables t;
     st = fused_tables(plan, &t);

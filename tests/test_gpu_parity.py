@@ -245,12 +245,15 @@ def test_capture_into_a_hip_graph_and_replay(dev):
     say("capturing")
     with torch.cuda.graph(graph, stream=side):
         D.ddl_allreduce_sim(bufs, P, plan, count, D.DDL_F32, torch.cuda.current_stream())
-    for replay in range(3):
+    fused_graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(fused_graph, stream=side):
+        D.ddl_allreduce_fused_sim(bufs, P, plan, count, D.DDL_F32, torch.cuda.current_stream())
+    for replay in range(4):
         say(f"replay {replay}")
         for b, v in zip(bufs, V):           # eager work between replays: restore the inputs
             b.copy_(torch.from_numpy(v))
         torch.cuda.synchronize()
-        graph.replay()
+        (graph if replay % 2 == 0 else fused_graph).replay()
         for j, g in enumerate(download(bufs)):
             assert_bitwise(g, want[j], f"replay {replay} learner={j}")
 
@@ -648,6 +651,27 @@ def run_config(dev, cfg, full_compare):
             worst_rel = max(worst_rel, float(np.max(err)) / max(float(np.max(np.abs(ref))), 1e-30))
     assert worst_rel <= 1e-5
     say(f"  ok, worst |x - fp64| / max|fp64| = {worst_rel:.2e}")
+
+
+def test_buffers_beyond_four_gibibytes(dev):
+    """Two learners of 4.8 GB each: element and byte offsets that do not fit 32 bits."""
+    P, dims, count, seed = 2, [2], 1_200_000_003, 4242
+    say(f"large buffers: P={P} count={count} ({4 * count / 2**30:.2f} GiB per learner)")
+    bufs = [torch.empty(count, dtype=torch.float32, device=dev) for _ in range(P)]
+    plan = D.ddl_ring_plan(dims, P, count)
+    rng = np.random.default_rng(1)
+    ranges = [(0, 4096), (count - 4099, count), (count // 2 - 2048, count // 2 + 2048),
+              (2 ** 30 - 1024, 2 ** 30 + 1024)] + [(int(a), int(a) + 2048) for a in rng.integers(0, count - 2048, 6)]
+    for entry in (D.ddl_allreduce_sim, D.ddl_allreduce_fused_sim):
+        for j, b in enumerate(bufs):
+            I.fill_device(b, seed, j, "uniform")
+        entry(bufs, P, plan, count, D.DDL_F32, torch.cuda.current_stream())
+        torch.cuda.synchronize()
+        assert torch.equal(bufs[0].view(torch.int32), bufs[1].view(torch.int32))
+        for a, b in ranges:
+            want = O.allreduce_fold_range(lambda r, lo, hi: I.fill_host(hi - lo, seed, r, "uniform", first=lo),
+                                          dims, count, a, b, np.float32)
+            assert_bitwise(bufs[1][a:b].cpu().numpy(), want, f"{entry.__name__} elements [{a},{b})")
 
 
 def test_config1_ring4_integer_exact(dev):
