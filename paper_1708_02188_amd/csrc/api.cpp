@@ -20,6 +20,35 @@ void set_status(ddl_status_t* status, ddl_status_t value) {
     if (status) *status = value;
 }
 
+template <typename T>
+void release(T** d) {
+    if (*d) (void)hipFree(*d);
+    *d = nullptr;
+}
+
+void release_tables(DeviceTables* t) {
+    release(&t->ops);
+    release(&t->rops);
+    release(&t->ptrs);
+    release(&t->descs);
+    release(&t->fused_seq);
+    release(&t->fused_ctl);
+    release(&t->fused_n);
+    release(&t->fused_off);
+    release(&t->fused_ptrs);
+}
+
+template <typename T>
+bool reserve(T** d, size_t count) {
+    return hipMalloc(reinterpret_cast<void**>(d), count * sizeof(T)) == hipSuccess;
+}
+
+template <typename T>
+bool upload(T** d, const std::vector<T>& h) {
+    return reserve(d, h.size()) &&
+           hipMemcpy(*d, h.data(), h.size() * sizeof(T), hipMemcpyHostToDevice) == hipSuccess;
+}
+
 // Device copies of the step tables for the current device, created on first use.
 ddl_status_t device_tables(const ddl_plan* plan, DeviceTables* out) {
     int device = -1;
@@ -32,36 +61,13 @@ ddl_status_t device_tables(const ddl_plan* plan, DeviceTables* out) {
         }
     DeviceTables t;
     t.device = device;
-    const size_t ops_bytes = plan->ops.size() * sizeof(Op);
-    if (ops_bytes) {
-        if (hipMalloc(reinterpret_cast<void**>(&t.ops), ops_bytes) != hipSuccess) return DDL_ERR_NOMEM;
-        if (hipMemcpy(t.ops, plan->ops.data(), ops_bytes, hipMemcpyHostToDevice) != hipSuccess) {
-            (void)hipFree(t.ops);
-            return DDL_ERR_HIP;
-        }
-        if (hipMalloc(reinterpret_cast<void**>(&t.rops),
-                      plan->ops.size() * sizeof(ddl::ResolvedOp)) != hipSuccess) {
-            (void)hipFree(t.ops);
-            return DDL_ERR_NOMEM;
-        }
-    }
-    if (!plan->descs.empty()) {
-        const size_t bytes = plan->descs.size() * sizeof(ddl::BlockDesc);
-        if (hipMalloc(reinterpret_cast<void**>(&t.descs), bytes) != hipSuccess ||
-            hipMemcpy(t.descs, plan->descs.data(), bytes, hipMemcpyHostToDevice) != hipSuccess) {
-            if (t.descs) (void)hipFree(t.descs);
-            if (t.ops) (void)hipFree(t.ops);
-            if (t.rops) (void)hipFree(t.rops);
-            return DDL_ERR_NOMEM;
-        }
-    }
-    if (plan->P > ddl::kKernargLearners) {
-        if (hipMalloc(reinterpret_cast<void**>(&t.ptrs), size_t(plan->P) * sizeof(void*)) != hipSuccess) {
-            if (t.ops) (void)hipFree(t.ops);
-            if (t.rops) (void)hipFree(t.rops);
-            if (t.descs) (void)hipFree(t.descs);
-            return DDL_ERR_NOMEM;
-        }
+    bool ok = true;
+    if (!plan->ops.empty()) ok = upload(&t.ops, plan->ops) && reserve(&t.rops, plan->ops.size());
+    if (ok && !plan->descs.empty()) ok = upload(&t.descs, plan->descs);
+    if (ok && plan->P > ddl::kKernargLearners) ok = reserve(&t.ptrs, size_t(plan->P));
+    if (!ok) {
+        release_tables(&t);
+        return DDL_ERR_NOMEM;
     }
     plan->tables.push_back(t);
     *out = t;
@@ -69,12 +75,6 @@ ddl_status_t device_tables(const ddl_plan* plan, DeviceTables* out) {
 }
 
 // Adds the tables of the step-fused path to the plan's entry for the current device.
-template <typename T>
-bool upload(T** d, const std::vector<T>& h) {
-    if (hipMalloc(reinterpret_cast<void**>(d), h.size() * sizeof(T)) != hipSuccess) return false;
-    return hipMemcpy(*d, h.data(), h.size() * sizeof(T), hipMemcpyHostToDevice) == hipSuccess;
-}
-
 ddl_status_t fused_tables(const ddl_plan* plan, DeviceTables* out) {
     DeviceTables base;
     ddl_status_t st = device_tables(plan, &base);
@@ -89,19 +89,13 @@ ddl_status_t fused_tables(const ddl_plan* plan, DeviceTables* out) {
             t.fused_padded = padded;
             const bool ok = upload(&t.fused_seq, seq) && upload(&t.fused_ctl, ctl) &&
                             upload(&t.fused_n, plan->own_n) && upload(&t.fused_off, plan->own_off) &&
-                            hipMalloc(reinterpret_cast<void**>(&t.fused_ptrs),
-                                      seq.size() * sizeof(uint64_t)) == hipSuccess;
+                            reserve(&t.fused_ptrs, seq.size());
             if (!ok) {
-                uint32_t** p32[] = {&t.fused_seq, &t.fused_ctl};
-                uint64_t** p64[] = {&t.fused_n, &t.fused_off, &t.fused_ptrs};
-                for (uint32_t** p : p32) {
-                    if (*p) (void)hipFree(*p);
-                    *p = nullptr;
-                }
-                for (uint64_t** p : p64) {
-                    if (*p) (void)hipFree(*p);
-                    *p = nullptr;
-                }
+                release(&t.fused_seq);
+                release(&t.fused_ctl);
+                release(&t.fused_n);
+                release(&t.fused_off);
+                release(&t.fused_ptrs);
                 return DDL_ERR_NOMEM;
             }
         }
@@ -235,17 +229,7 @@ ddl_plan_t* ddl_ring_plan_tensors(const int* dims, int m, int P, const size_t* t
 
 void ddl_plan_free(ddl_plan_t* plan) {
     if (plan == nullptr) return;
-    for (const DeviceTables& t : plan->tables) {
-        if (t.ops) (void)hipFree(t.ops);
-        if (t.rops) (void)hipFree(t.rops);
-        if (t.ptrs) (void)hipFree(t.ptrs);
-        if (t.descs) (void)hipFree(t.descs);
-        if (t.fused_seq) (void)hipFree(t.fused_seq);
-        if (t.fused_ctl) (void)hipFree(t.fused_ctl);
-        if (t.fused_n) (void)hipFree(t.fused_n);
-        if (t.fused_off) (void)hipFree(t.fused_off);
-        if (t.fused_ptrs) (void)hipFree(t.fused_ptrs);
-    }
+    for (DeviceTables& t : plan->tables) release_tables(&t);
     delete plan;
 }
 
