@@ -68,6 +68,9 @@ enum { DDL_STEP_REDUCE = 0, DDL_STEP_GATHER = 1 };
 #define DDL_MAX_LEARNERS 65535
 #define DDL_MAX_DIMS 16
 #define DDL_MAX_TENSORS 65536
+/* A plan stores phases x tensors x learners operations (56 bytes each, host + device);
+ * plans beyond this many are refused with DDL_ERR_NOMEM. */
+#define DDL_MAX_PLAN_OPS (1ull << 26)
 
 /*
  * Build the schedule for a box dims[0..m-1] (Sec. 4.3: N = d_1*...*d_m) over P learners

@@ -187,6 +187,12 @@ ddl_plan_t* make_plan(const int* dims, int m, int P, const size_t* seg_off, cons
         else if (seg_off[s] < end || seg_count[s] > count || seg_off[s] > count - seg_count[s]) st = DDL_ERR_ARG;
         end = seg_off[s] + seg_count[s];
     }
+    if (st == DDL_OK) {
+        // the schedule is held as explicit tables: phases x tensors x learners operations
+        uint64_t phases = 0;
+        for (int t = 0; t < m; ++t) phases += 2 * uint64_t(dims[t] - 1);
+        if (phases * uint64_t(S) > DDL_MAX_PLAN_OPS / uint64_t(P)) st = DDL_ERR_NOMEM;
+    }
     if (st != DDL_OK) {
         set_status(status, st);
         return nullptr;

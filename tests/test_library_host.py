@@ -115,6 +115,11 @@ def test_plan_argument_errors():
     assert status_of(D.ddl_ring_plan, [4], 4, 10, 99) == D.DDL_ERR_DTYPE
     assert status_of(D.ddl_ring_plan, None, 4, 10) == D.DDL_ERR_ARG
     assert status_of(D.ddl_ring_plan, [65536], 65536, 10) == D.DDL_ERR_ARG
+    # a flat ring of 65535 learners would need 8.6e9 table entries: refused, not attempted
+    assert status_of(D.ddl_ring_plan, [65535], 65535, 10) == D.DDL_ERR_NOMEM
+    big = D.ddl_ring_plan([15, 17, 257], 65535, 10)   # the largest learner count, as a box
+    assert D.ddl_plan_num_steps(big) == 2 * (14 + 16 + 256)
+    D.ddl_plan_free(big)
     for code in range(-8, 1):
         assert D.ddl_status_string(code) and D.ddl_status_string(code) != "unknown status"
     assert D.ddl_status_string(-99) == "unknown status"
