@@ -160,15 +160,19 @@ def test_other_dtypes_match_step_simulator(dev, dtype, dims, count):
         assert_bitwise(got[j], want[j], f"dtype={dtype} dims={dims} learner={j}")
 
 
-def test_hand_worked_example_on_device(dev):
+@pytest.mark.parametrize("name", ["ring4_cancellation.txt", "box2x2_dimension_order.txt"])
+def test_hand_worked_examples_on_device(dev, name):
     from conftest import read_golden_ring_example
-    ex = read_golden_ring_example("ring4_cancellation.txt")
-    V = [np.full(16, v, dtype=np.float32) for v in ex["inputs"]]
-    bufs = upload(V, dev)
-    plan = D.ddl_ring_plan(ex["dims"], 4, 16)
-    D.ddl_allreduce_sim(bufs, 4, plan, 16)
-    for g in download(bufs):
-        assert np.array_equal(g, np.array(ex["expected"], dtype=np.float32))
+    ex = read_golden_ring_example(name)
+    n = len(ex["expected"])
+    V = [np.full(n, v, dtype=np.float32) for v in ex["inputs"]]
+    want = np.array(ex["expected"], dtype=np.float32)
+    plan = D.ddl_ring_plan(ex["dims"], 4, n)
+    for entry in (D.ddl_allreduce_sim, D.ddl_allreduce_fused_sim):
+        bufs = upload(V, dev)
+        entry(bufs, 4, plan, n)
+        for g in download(bufs):
+            assert np.array_equal(g, want), (name, entry.__name__, g)
 
 
 # ---------------------------------------------------------------------------------------

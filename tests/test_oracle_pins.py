@@ -110,13 +110,14 @@ def test_steps_equal_fold_bitwise():
 # T4: the hand-worked example
 # ---------------------------------------------------------------------------------------
 def pin_hand_worked_example():
-    ex = read_golden_ring_example("ring4_cancellation.txt")
-    n = len(ex["expected"])
-    V = [np.full(n, v, dtype=np.float32) for v in ex["inputs"]]
-    want = np.array(ex["expected"], dtype=np.float32)
-    for g in O.allreduce_steps(V, ex["dims"]):
-        assert np.array_equal(g, want), g
-    assert np.array_equal(O.allreduce_fold(V, ex["dims"]), want)
+    for name in ("ring4_cancellation.txt", "box2x2_dimension_order.txt"):
+        ex = read_golden_ring_example(name)
+        n = len(ex["expected"])
+        V = [np.full(n, v, dtype=np.float32) for v in ex["inputs"]]
+        want = np.array(ex["expected"], dtype=np.float32)
+        for g in O.allreduce_steps(V, ex["dims"]):
+            assert np.array_equal(g, want), (name, g)
+        assert np.array_equal(O.allreduce_fold(V, ex["dims"]), want), name
 
 
 def test_hand_worked_example():
@@ -435,6 +436,8 @@ def test_mutation_transposed_coordinates(monkeypatch):
     pin_bruteforce_integer_sum(**SMALL)
     with pytest.raises(AssertionError):
         pin_all_twos_is_pairwise_tree()
+    with pytest.raises(AssertionError):
+        pin_hand_worked_example()
 
 
 def test_mutation_wrong_direction_only_in_neighbour(monkeypatch):
