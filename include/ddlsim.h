@@ -182,6 +182,21 @@ ddl_status_t ddl_allreduce_sim_timed(void** bufs, int P, const ddl_plan_t* plan,
 ddl_status_t ddl_allreduce_fused_sim(void** bufs, int P, const ddl_plan_t* plan, size_t count,
                                      ddl_dtype_t dtype, void* stream);
 
+/*
+ * The two passes of the step-fused form as operations of their own (Sec. 4.1 ReduceScatter
+ * and AllGather, each in one kernel pass); same arguments, limits and errors as
+ * ddl_allreduce_fused_sim.
+ * ddl_reduce_scatter_fused_sim: learner r's finest chunk (ddl_plan_owned_chunk) receives the
+ * sum over all learners in the schedule's summation order; nothing else is written (unlike
+ * ddl_reduce_scatter_sim, which leaves the phases' partial sums in the other chunks).
+ * ddl_allgather_fused_sim: every learner's finest chunk is copied into all other learners.
+ * One after the other they give exactly ddl_allreduce_sim's final state.
+ */
+ddl_status_t ddl_reduce_scatter_fused_sim(void** bufs, int P, const ddl_plan_t* plan, size_t count,
+                                          ddl_dtype_t dtype, void* stream);
+ddl_status_t ddl_allgather_fused_sim(void** bufs, int P, const ddl_plan_t* plan, size_t count,
+                                     ddl_dtype_t dtype, void* stream);
+
 /* ---- plan introspection (host only) ------------------------------------------------ */
 
 /* 2 * sum_t (d_t - 1): Sec. 4.3, d-1 phases per ring, once reducing and once gathering.

@@ -49,6 +49,8 @@ def _load():
         "ddl_reduce_scatter_sim": (i, sim_args),
         "ddl_allgather_sim": (i, sim_args),
         "ddl_allreduce_fused_sim": (i, sim_args),
+        "ddl_reduce_scatter_fused_sim": (i, sim_args),
+        "ddl_allgather_fused_sim": (i, sim_args),
         "ddl_plan_fused_bytes": (sz, [vp]),
         "ddl_allreduce_sim_profile": (i, sim_args + [ctypes.POINTER(ctypes.c_float)]),
         "ddl_allreduce_sim_timed": (i, sim_args + [ctypes.POINTER(ctypes.c_float),
@@ -184,6 +186,16 @@ def ddl_allgather_sim(bufs, P, plan, count, dtype=DDL_F32, stream=None):
 def ddl_allreduce_fused_sim(bufs, P, plan, count, dtype=DDL_F32, stream=None):
     _check(_lib.ddl_allreduce_fused_sim(_ptr_array(bufs), P, _h(plan), count, dtype, _stream(stream)),
            "ddl_allreduce_fused_sim")
+
+
+def ddl_reduce_scatter_fused_sim(bufs, P, plan, count, dtype=DDL_F32, stream=None):
+    _check(_lib.ddl_reduce_scatter_fused_sim(_ptr_array(bufs), P, _h(plan), count, dtype, _stream(stream)),
+           "ddl_reduce_scatter_fused_sim")
+
+
+def ddl_allgather_fused_sim(bufs, P, plan, count, dtype=DDL_F32, stream=None):
+    _check(_lib.ddl_allgather_fused_sim(_ptr_array(bufs), P, _h(plan), count, dtype, _stream(stream)),
+           "ddl_allgather_fused_sim")
 
 
 def ddl_plan_fused_bytes(plan):

@@ -276,8 +276,11 @@ ddl_status_t ddl_allgather_sim(void** bufs, int P, const ddl_plan_t* plan, size_
     return run_steps(bufs, P, plan, count, dtype, stream, split, steps, nullptr);
 }
 
-ddl_status_t ddl_allreduce_fused_sim(void** bufs, int P, const ddl_plan_t* plan, size_t count,
-                                     ddl_dtype_t dtype, void* stream_v) {
+namespace {
+
+// which: 0 = whole allreduce, 1 = reducing pass only, 2 = distributing pass only
+ddl_status_t run_fused(void** bufs, int P, const ddl_plan* plan, size_t count, ddl_dtype_t dtype,
+                       void* stream_v, int which) {
     ddl_status_t st = check_call(bufs, P, plan, count, dtype);
     if (st != DDL_OK) return st;
     if (!fused_supported(plan)) return DDL_ERR_UNSUPPORTED;
@@ -301,18 +304,36 @@ ddl_status_t ddl_allreduce_fused_sim(void** bufs, int P, const ddl_plan_t* plan,
         return DDL_ERR_HIP;
     uint64_t max_chunk = 0;
     for (uint64_t n : plan->own_n) max_chunk = n > max_chunk ? n : max_chunk;
+    auto pass = [&](int mode) {
+        return ddl::launch_fused(*plan, t, t.fused_padded, t.fused_levels, max_chunk, mode, stream) == hipSuccess;
+    };
     // Measured on MI355X: from about 32 learners on, two passes (all reads of the reduction
     // first, then all writes of the distribution) sustain more bandwidth than one pass that
     // mixes P read and P write streams, at the price of writing and re-reading the result
     // once (1/P more traffic); below that the second launch costs more than it gains.
-    if (P >= 32) {
-        if (ddl::launch_fused(*plan, t, t.fused_padded, t.fused_levels, max_chunk, 1, stream) != hipSuccess ||
-            ddl::launch_fused(*plan, t, t.fused_padded, t.fused_levels, max_chunk, 2, stream) != hipSuccess)
-            return DDL_ERR_HIP;
-    } else if (ddl::launch_fused(*plan, t, t.fused_padded, t.fused_levels, max_chunk, 0, stream) != hipSuccess) {
-        return DDL_ERR_HIP;
-    }
-    return DDL_OK;
+    bool ok;
+    if (which == 1) ok = pass(1);
+    else if (which == 2) ok = pass(2);
+    else if (P >= 32) ok = pass(1) && pass(2);
+    else ok = pass(0);
+    return ok ? DDL_OK : DDL_ERR_HIP;
+}
+
+}  // namespace
+
+ddl_status_t ddl_allreduce_fused_sim(void** bufs, int P, const ddl_plan_t* plan, size_t count,
+                                     ddl_dtype_t dtype, void* stream) {
+    return run_fused(bufs, P, plan, count, dtype, stream, 0);
+}
+
+ddl_status_t ddl_reduce_scatter_fused_sim(void** bufs, int P, const ddl_plan_t* plan, size_t count,
+                                          ddl_dtype_t dtype, void* stream) {
+    return run_fused(bufs, P, plan, count, dtype, stream, 1);
+}
+
+ddl_status_t ddl_allgather_fused_sim(void** bufs, int P, const ddl_plan_t* plan, size_t count,
+                                     ddl_dtype_t dtype, void* stream) {
+    return run_fused(bufs, P, plan, count, dtype, stream, 2);
 }
 
 ddl_status_t ddl_allreduce_sim_profile(void** bufs, int P, const ddl_plan_t* plan, size_t count,

@@ -559,6 +559,29 @@ def test_fused_allreduce_other_dtypes(dev, dtype, dims, count):
         assert_bitwise(got[j], want, f"fused dtype={dtype} dims={dims} learner={j}")
 
 
+@pytest.mark.parametrize("dims,count", [([4], 20003), ([2, 3], 9001), ([4, 2, 2], 100001), ([4, 8, 8], 300001)])
+def test_fused_halves_alone(dev, dims, count):
+    """ReduceScatter / AllGather as single passes: owner's chunk = the schedule-order sum,
+    nothing else written; then every owner's chunk copied everywhere."""
+    P = prod(dims)
+    say(f"fused halves dims={dims} count={count}")
+    rng = np.random.default_rng(77)
+    V = wide_inputs(rng, P, count, D.DDL_F32)
+    fold = O.allreduce_fold(V, dims)
+    plan = D.ddl_ring_plan(dims, P, count)
+    bufs = upload(V, dev)
+    D.ddl_reduce_scatter_fused_sim(bufs, P, plan, count)
+    got = download(bufs)
+    for j in range(P):
+        want = V[j].copy()
+        off, n = D.ddl_plan_owned_chunk(plan, j)
+        want[off:off + n] = fold[off:off + n]
+        assert_bitwise(got[j], want, f"fused reduce-scatter learner={j}")
+    D.ddl_allgather_fused_sim(bufs, P, plan, count)
+    for j, g in enumerate(download(bufs)):
+        assert_bitwise(g, fold, f"fused all-gather learner={j}")
+
+
 def test_fused_allreduce_many_learners_and_limits(dev):
     dims, count, P = [8, 8, 8], 70001, 512
     V = [I.fill_host(count, 5, j, "uniform") for j in range(P)]

@@ -130,7 +130,8 @@ def test_plan_argument_errors():
 
 @pytest.mark.parametrize("entry", [D.ddl_allreduce_sim, D.ddl_reduce_scatter_sim,
                                    D.ddl_allgather_sim, D.ddl_allreduce_sim_profile,
-                                   D.ddl_allreduce_sim_timed, D.ddl_allreduce_fused_sim])
+                                   D.ddl_allreduce_sim_timed, D.ddl_allreduce_fused_sim,
+                                   D.ddl_reduce_scatter_fused_sim, D.ddl_allgather_fused_sim])
 def test_call_argument_errors(entry):
     count = 64
     plan = D.ddl_ring_plan([2, 2], 4, count)
