@@ -164,6 +164,15 @@ ddl_status_t ddl_allreduce_sim_timed(void** bufs, int P, const ddl_plan_t* plan,
                                      float* gather_ms);
 
 /*
+ * Assignment (Sec. 4.1: "the most basic operation", object A receives a copy of object B):
+ * dst[0 .. count) <- src[0 .. count), both DEVICE pointers, 16-byte aligned, not
+ * overlapping, with the copy kernel of the all-gather phases.  Needs no plan.  Enqueued on
+ * `stream`, does not synchronise.  DDL_ERR_ARG for NULL or overlapping ranges (count > 0),
+ * DDL_ERR_ALIGN, DDL_ERR_DTYPE, DDL_ERR_HIP.
+ */
+ddl_status_t ddl_assign_sim(void* dst, const void* src, size_t count, ddl_dtype_t dtype, void* stream);
+
+/*
  * Step-fused allreduce: the same final state as ddl_allreduce_sim (every learner holds the
  * sum, bit for bit the value the schedule's summation order gives) produced in ONE pass
  * that reads every learner's element once, folds the ring orders of all dimensions in

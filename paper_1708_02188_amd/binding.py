@@ -48,6 +48,7 @@ def _load():
         "ddl_allreduce_sim": (i, sim_args),
         "ddl_reduce_scatter_sim": (i, sim_args),
         "ddl_allgather_sim": (i, sim_args),
+        "ddl_assign_sim": (i, [vp, vp, sz, i, vp]),
         "ddl_allreduce_fused_sim": (i, sim_args),
         "ddl_reduce_scatter_fused_sim": (i, sim_args),
         "ddl_allgather_fused_sim": (i, sim_args),
@@ -186,6 +187,12 @@ def ddl_allgather_sim(bufs, P, plan, count, dtype=DDL_F32, stream=None):
 def ddl_allreduce_fused_sim(bufs, P, plan, count, dtype=DDL_F32, stream=None):
     _check(_lib.ddl_allreduce_fused_sim(_ptr_array(bufs), P, _h(plan), count, dtype, _stream(stream)),
            "ddl_allreduce_fused_sim")
+
+
+def ddl_assign_sim(dst, src, count, dtype=DDL_F32, stream=None):
+    d = dst.data_ptr() if hasattr(dst, "data_ptr") else dst
+    s = src.data_ptr() if hasattr(src, "data_ptr") else src
+    _check(_lib.ddl_assign_sim(d, s, count, dtype, _stream(stream)), "ddl_assign_sim")
 
 
 def ddl_reduce_scatter_fused_sim(bufs, P, plan, count, dtype=DDL_F32, stream=None):

@@ -321,6 +321,19 @@ ddl_status_t run_fused(void** bufs, int P, const ddl_plan* plan, size_t count, d
 
 }  // namespace
 
+ddl_status_t ddl_assign_sim(void* dst, const void* src, size_t count, ddl_dtype_t dtype, void* stream) {
+    const int elem = ddl::dtype_size(dtype);
+    if (elem == 0) return DDL_ERR_DTYPE;
+    if (count == 0) return DDL_OK;
+    if (dst == nullptr || src == nullptr) return DDL_ERR_ARG;
+    const uintptr_t d = reinterpret_cast<uintptr_t>(dst), s = reinterpret_cast<uintptr_t>(src);
+    if (d % 16 != 0 || s % 16 != 0) return DDL_ERR_ALIGN;
+    const uintptr_t bytes = uintptr_t(count) * uintptr_t(elem);
+    if ((d <= s && s < d + bytes) || (s <= d && d < s + bytes)) return DDL_ERR_ARG;
+    return ddl::launch_assign(dtype, dst, src, count, static_cast<hipStream_t>(stream)) == hipSuccess
+               ? DDL_OK : DDL_ERR_HIP;
+}
+
 ddl_status_t ddl_allreduce_fused_sim(void** bufs, int P, const ddl_plan_t* plan, size_t count,
                                      ddl_dtype_t dtype, void* stream) {
     return run_fused(bufs, P, plan, count, dtype, stream, 0);

@@ -26,6 +26,9 @@ hipError_t launch_resolve(const ddl_plan& plan, const Op* d_ops, ResolvedOp* d_r
 hipError_t launch_step(const ddl_plan& plan, const Step& step, const ResolvedOp* d_rops,
                        const BlockDesc* d_descs, hipStream_t stream);
 
+// Plain copy of n elements with the all-gather phase's streaming shape.
+hipError_t launch_assign(ddl_dtype_t dtype, void* dst, const void* src, uint64_t n, hipStream_t stream);
+
 // Step-fused allreduce.  launch_fused_resolve binds the summation-order table to the
 // caller's buffers: d_ptrs_out[c * padded + i] = address of finest chunk c in learner
 // seq[c][i].  launch_fused runs the single pass over all chunks.

@@ -206,6 +206,34 @@ __global__ __launch_bounds__(DDL_THREADS) void step_kernel(const ResolvedOp* __r
         step_tile<T, REDUCE>(src, dst, n, nv, first, threadIdx.x);
 }
 
+// Assignment of one buffer to another: the copy phase for a single operation whose record
+// arrives as kernel arguments.
+template <typename T>
+__global__ __launch_bounds__(DDL_THREADS) void assign_kernel(uint64_t src_addr, uint64_t dst_addr, uint64_t n_,
+                                                             unsigned tile_stride) {
+    typedef typename Elem<T>::V V;
+    constexpr int64_t VL = 16 / sizeof(typename Elem<T>::S);
+    constexpr int64_t TILE = int64_t(DDL_THREADS) * DDL_UNROLL;
+    const int64_t n = int64_t(n_);
+    const int64_t nv = n / VL;
+    const int64_t shift = int64_t((dst_addr % kRowBytes) / 16);
+    for (int64_t first = int64_t(blockIdx.x) * TILE - shift; first <= nv; first += int64_t(tile_stride) * TILE)
+        step_tile<T, false>((const DDL_GLOBAL V*)src_addr, (DDL_GLOBAL V*)dst_addr, n, nv, first, threadIdx.x);
+}
+
+template <typename T>
+hipError_t launch_assign_typed(void* dst, const void* src, uint64_t n, hipStream_t stream) {
+    constexpr uint64_t VL = 16 / sizeof(typename Elem<T>::S);
+    constexpr uint64_t TILE = uint64_t(DDL_THREADS) * DDL_UNROLL;
+    uint64_t tiles = (n / VL + 1 + (kRowVecs - 1) + TILE - 1) / TILE;
+    const uint64_t max_x = (uint64_t(1) << 32) / DDL_THREADS - 1;
+    if (tiles > max_x) tiles = max_x;
+    hipLaunchKernelGGL((assign_kernel<T>), dim3(static_cast<unsigned>(tiles)), dim3(DDL_THREADS), 0, stream,
+                       reinterpret_cast<uint64_t>(src), reinterpret_cast<uint64_t>(dst), n,
+                       static_cast<unsigned>(tiles));
+    return hipGetLastError();
+}
+
 // Several-tensor plans: the phase's transfers differ in length by orders of magnitude, so
 // the launch is a flat list of work items (operation, first row).  Items that hold all
 // kListRows rows come first and get one single-wave workgroup per row, like the
@@ -478,6 +506,18 @@ hipError_t launch_step(const ddl_plan& plan, const Step& step, const ResolvedOp*
         case DDL_I32: return launch_typed<unsigned>(plan, step, d_rops, stream);
         case DDL_F16: return launch_typed<_Float16>(plan, step, d_rops, stream);
         case DDL_BF16: return launch_typed<bf16_bits>(plan, step, d_rops, stream);
+    }
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_assign(ddl_dtype_t dtype, void* dst, const void* src, uint64_t n, hipStream_t stream) {
+    if (n == 0) return hipSuccess;
+    switch (dtype) {
+        case DDL_F32: return launch_assign_typed<float>(dst, src, n, stream);
+        case DDL_F64: return launch_assign_typed<double>(dst, src, n, stream);
+        case DDL_I32: return launch_assign_typed<unsigned>(dst, src, n, stream);
+        case DDL_F16: return launch_assign_typed<_Float16>(dst, src, n, stream);
+        case DDL_BF16: return launch_assign_typed<bf16_bits>(dst, src, n, stream);
     }
     return hipErrorInvalidValue;
 }

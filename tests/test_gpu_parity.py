@@ -314,6 +314,20 @@ def test_counts_around_row_and_tile_edges(dev):
                 assert_bitwise(g, want[j], f"dtype={dtype} count={count} learner={j}")
 
 
+def test_assignment(dev):
+    """Sec. 4.1's basic operation: B copied into A, other memory untouched."""
+    for dtype, tdt in ((D.DDL_F32, torch.float32), (D.DDL_F64, torch.float64), (D.DDL_F16, torch.float16)):
+        esz = torch.empty(0, dtype=tdt).element_size()
+        G = 16 // esz
+        for count in (1, G - 1, 64 * G, 64 * G + 1, 100003, 3 * 64 * G * 5 + 7):
+            src = (torch.arange(count + 2 * G, device=dev) % 251).to(tdt)
+            dst = torch.full((count + 4 * G,), -1, dtype=tdt, device=dev)
+            D.ddl_assign_sim(dst[2 * G:], src[G:], count, dtype, torch.cuda.current_stream())
+            torch.cuda.synchronize()
+            assert torch.equal(dst[2 * G:2 * G + count], src[G:G + count]), (dtype, count)
+            assert bool((dst[:2 * G] == -1).all()) and bool((dst[2 * G + count:] == -1).all()), (dtype, count)
+
+
 def test_buckets_on_two_streams(dev):
     """A gradient buffer cut into two buckets, each with its own plan on its own stream
     (how a framework would overlap the allreduce of early layers with later compute)."""

@@ -149,6 +149,16 @@ def test_call_argument_errors(entry):
     assert status_of(entry, [good[0], good[0] + 128, good[2], good[3]], 4, plan, count) == D.DDL_ERR_ARG
 
 
+def test_assign_argument_errors():
+    a, b = 0x100000, 0x200000
+    assert status_of(D.ddl_assign_sim, a, b, 100, 77) == D.DDL_ERR_DTYPE
+    assert status_of(D.ddl_assign_sim, None, b, 100) == D.DDL_ERR_ARG
+    assert status_of(D.ddl_assign_sim, a + 4, b, 100) == D.DDL_ERR_ALIGN
+    assert status_of(D.ddl_assign_sim, a, a + 16, 100) == D.DDL_ERR_ARG     # overlapping
+    assert status_of(D.ddl_assign_sim, a, a, 100) == D.DDL_ERR_ARG
+    D.ddl_assign_sim(None, None, 0)                                          # nothing to copy
+
+
 def test_fused_limits_and_bytes():
     plan = D.ddl_ring_plan([4, 8, 8], 256, 25557032)
     assert D.ddl_plan_fused_bytes(plan) == 4 * 25557032 * (2 * 256 + 2)
