@@ -324,3 +324,57 @@ def test_tensor_plan_argument_errors():
     assert status_of(D.ddl_plan_owned_chunk_tensor, plan, 2, 0) == D.DDL_ERR_ARG
     ptrs = [0x100000 + 0x1000 * j for j in range(4)]
     assert status_of(D.ddl_allreduce_fused_sim, ptrs, 4, plan, 100) == D.DDL_ERR_UNSUPPORTED
+
+
+# ---------------------------------------------------------------------------------------
+# property test: planner tables == oracle schedule on random boxes, lengths and tensor lists
+# ---------------------------------------------------------------------------------------
+from hypothesis import given, settings, strategies as st  # noqa: E402
+
+
+@st.composite
+def plan_cases(draw):
+    dims = draw(st.lists(st.integers(1, 6), min_size=1, max_size=4))
+    itemsize = draw(st.sampled_from([2, 4, 8]))
+    G = 16 // itemsize
+    n_tensors = draw(st.integers(1, 5))
+    segments, pos = [], 0
+    for _ in range(n_tensors):
+        pos += draw(st.integers(0, 3)) * G
+        n = draw(st.one_of(st.integers(0, 40), st.integers(0, 5000)))
+        segments.append((pos, n))
+        pos = -(-(pos + n) // G) * G
+    count = pos + draw(st.integers(0, 9))
+    return dims, itemsize, segments, count
+
+
+@settings(max_examples=150, deadline=None)
+@given(plan_cases())
+def test_planner_matches_oracle_on_random_cases(case):
+    dims, itemsize, segments, count = case
+    P = prod(dims)
+    dtype = {2: D.DDL_F16, 4: D.DDL_F32, 8: D.DDL_F64}[itemsize]
+    G = 16 // itemsize
+    if len(segments) == 1 and segments[0][0] == 0:
+        count = segments[0][1]
+        plan = D.ddl_ring_plan(dims, P, count, dtype)
+    else:
+        plan = D.ddl_ring_plan_tensors(dims, P, [o for o, _ in segments], [n for _, n in segments], count, dtype)
+    steps = O.schedule_tensors(dims, segments, G)
+    assert D.ddl_plan_num_steps(plan) == len(steps)
+    total = 0
+    for i, (kind, t, ops) in enumerate(steps):
+        k, dim, lib_ops = D.ddl_plan_get_step(plan, i)
+        assert (k, dim) == (D.DDL_STEP_REDUCE if kind == "RS" else D.DDL_STEP_GATHER, t)
+        assert lib_ops == [(src, dst, a, b - a) for src, dst, a, b in ops]
+        total += sum(b - a for _, _, a, b in ops) * (3 if kind == "RS" else 2) * itemsize
+    assert D.ddl_plan_bytes_moved(plan) == total
+    # within a phase no learner's written range meets a range it is read from
+    for _, _, ops in steps:
+        writes = {}
+        for src, dst, a, b in ops:
+            if b > a:
+                writes.setdefault(dst, []).append((a, b))
+        for src, dst, a, b in ops:
+            for wa, wb in writes.get(src, []):
+                assert b <= wa or wb <= a or a == b
