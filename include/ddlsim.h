@@ -40,8 +40,8 @@ typedef struct ddl_plan ddl_plan_t;
 
 /* Element types.  Sums are formed in the element type itself, one rounding per addition,
  * round-to-nearest-even (the paper speaks of "floating point entries" of 4 bytes: 90 M
- * entries = 350 MB).  The 16-bit types are added in binary32 and rounded once to 16 bits,
- * which equals the correctly rounded 16-bit sum. */
+ * entries = 350 MB).  For the 16-bit types that is the correctly rounded 16-bit sum (bf16
+ * is widened to binary32, added there and rounded once, which gives the same value). */
 typedef enum {
     DDL_F32 = 0,
     DDL_F64 = 1,
@@ -55,7 +55,7 @@ typedef enum {
     DDL_ERR_ARG = -1,           /* NULL pointer, P < 1, duplicate buffers, bad step index   */
     DDL_ERR_DIMS = -2,          /* m < 1, a dimension < 1, or product of dims != P          */
     DDL_ERR_DTYPE = -3,         /* unknown element type                                     */
-    DDL_ERR_ALIGN = -4,         /* a learner buffer is not 16-byte aligned                  */
+    DDL_ERR_ALIGN = -4,         /* a buffer or a tensor's start is not 16-byte aligned      */
     DDL_ERR_PLAN_MISMATCH = -5, /* P / count / dtype differ from what the plan was made for */
     DDL_ERR_NOMEM = -6,         /* host or device allocation failed                         */
     DDL_ERR_HIP = -7,           /* a HIP runtime call failed (no device, launch error, ...) */
@@ -64,7 +64,7 @@ typedef enum {
 
 enum { DDL_STEP_REDUCE = 0, DDL_STEP_GATHER = 1 };
 
-/* Largest supported number of learners and box dimensions. */
+/* Largest supported numbers of learners, box dimensions and tensors per buffer. */
 #define DDL_MAX_LEARNERS 65535
 #define DDL_MAX_DIMS 16
 #define DDL_MAX_TENSORS 65536
