@@ -32,8 +32,18 @@ PIN STATUS
     message-passing simulator `allreduce_steps` and the per-element nested fold
     `allreduce_fold`), a hand-worked cancellation example, and the all-dims-2
     case, which must equal a pairwise (binary tree) summation.
-  * `multiring_time_model`: parity unpinned (the paper prints the formula for one
-    ring only; the multi-dimensional extension is a reading).
+  * `multiring_time_model`, `choose_dims_bruteforce`: parity unpinned (the paper
+    prints the formula for one ring only and says only that the dimensions are
+    adjusted to the links; the multi-dimensional estimate and the exhaustive
+    search over it are readings).  `ring_time_model` is the printed sum, pinned
+    to its closed form and to the figures the paper states.
+  * `allreduce_tensors` / `schedule_tensors` (several tensors per buffer): the
+    definition is the single-tensor oracle applied tensor by tensor; the batched
+    phase list is pinned to that definition and to integer sums.
+  * `bf16_add`, `f32_to_bf16`, `bf16_to_f32`: pinned to torch's CPU bfloat16
+    conversion and addition; fp16 uses numpy's own half arithmetic.
+  * Two hand-worked fp32 examples (tests/golden): one ring of four (order inside
+    a ring) and a 2 x 2 box (which learners share a ring of dimension 1).
 """
 from __future__ import annotations
 
