@@ -18,3 +18,19 @@ def test_world_size_from_the_launcher_is_refused_too():
     run = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py")], capture_output=True, text=True,
                          timeout=120, env=env)
     assert run.returncode == 2 and "ONE GPU" in run.stderr
+
+
+def test_missing_library_fails_loudly_and_there_is_no_fallback(tmp_path):
+    env = dict(os.environ, DDLSIM_LIBRARY=str(tmp_path / "nowhere" / "libddlsim.so"))
+    code = "import paper_1708_02188_amd as D\nD.ddl_ring_plan([2], 2, 8)\n"
+    run = subprocess.run([sys.executable, "-c", code], cwd=ROOT, capture_output=True, text=True,
+                         timeout=240, env=env)
+    assert run.returncode != 0
+    assert "ImportError" in run.stderr and "no fallback" in run.stderr
+    # nothing in the package imports the oracle
+    pkg = os.path.join(ROOT, "paper_1708_02188_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".cpp", ".h")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "import oracle" not in text and "from oracle" not in text, f
