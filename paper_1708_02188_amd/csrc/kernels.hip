@@ -237,8 +237,8 @@ hipError_t launch_assign_typed(void* dst, const void* src, uint64_t n, hipStream
 // Several-tensor plans: the phase's transfers differ in length by orders of magnitude, so
 // the launch is a flat list of work items (operation, first row).  Items that hold all
 // kListRows rows come first and get one single-wave workgroup per row, like the
-// single-tensor kernel; the ragged last item of each operation gets four workgroups that
-// share its rows.
+// single-tensor kernel; the short items that hold the rest of each operation (all there
+// is of a tiny tensor's chunk) get one workgroup each, which walks their kListTailRows rows.
 template <typename T, bool REDUCE>
 __global__ __launch_bounds__(64) void step_kernel_list(const ResolvedOp* __restrict__ rops,
                                                        const BlockDesc* __restrict__ descs,
@@ -250,7 +250,7 @@ __global__ __launch_bounds__(64) void step_kernel_list(const ResolvedOp* __restr
     const unsigned b = blockIdx.x + block_offset;
     const bool whole = b < whole_blocks;
     const unsigned t = b - whole_blocks;
-    const BlockDesc item = descs[whole ? b / kListRows : whole_items + t / 4];
+    const BlockDesc item = descs[whole ? b / kListRows : whole_items + t];
     const u64x4 rec = *reinterpret_cast<const u64x4*>(rops + item.op);
     const DDL_GLOBAL V* src = (const DDL_GLOBAL V*)rec.x;
     DDL_GLOBAL V* dst = (DDL_GLOBAL V*)rec.y;
@@ -262,7 +262,7 @@ __global__ __launch_bounds__(64) void step_kernel_list(const ResolvedOp* __restr
         if (first <= nv) step_tile<T, REDUCE>(src, dst, n, nv, first, threadIdx.x);
         return;
     }
-    for (int k = t % 4; k < kListRows; k += 4) {
+    for (int k = 0; k < kListTailRows; ++k) {
         const int64_t first = (int64_t(item.row) + k) * 64 - shift;
         if (first > nv) break;
         step_tile<T, REDUCE>(src, dst, n, nv, first, threadIdx.x);
@@ -274,7 +274,7 @@ hipError_t launch_list_typed(const Step& step, const ResolvedOp* d_rops, const B
                              hipStream_t stream) {
     if (step.desc_count == 0) return hipSuccess;
     const uint64_t whole_blocks = uint64_t(step.desc_whole) * kListRows;
-    const uint64_t blocks = whole_blocks + uint64_t(step.desc_count - step.desc_whole) * 4;
+    const uint64_t blocks = whole_blocks + uint64_t(step.desc_count - step.desc_whole);
     if (blocks > 0xFFFFFFFFull) return hipErrorInvalidValue;
     // one launch holds at most 2^26 - 1 workgroups (64 threads each, below 2^32 threads)
     const uint64_t per_launch = (uint64_t(1) << 26) - 1;

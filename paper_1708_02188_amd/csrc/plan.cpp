@@ -100,14 +100,15 @@ void build_schedule(ddl_plan* plan) {
                     // work list for the batched launch: spans of kListRows 1 KiB rows; one
                     // row more than the vectors need, because the tiling is shifted onto
                     // absolute row boundaries at run time.  Whole spans go to the front of
-                    // the phase's slice, the ragged last span of each operation to its back.
+                    // the phase's slice; what is left of each operation is cut into short
+                    // spans of kListTailRows rows that go to its back.
                     const uint64_t rows = (op.n / G + 1 + 63 + 63) / 64;
                     const uint32_t index = static_cast<uint32_t>(plan->ops.size() % (size_t(S) * P));
-                    for (uint64_t row = 0; row < rows; row += kListRows) {
-                        const BlockDesc item{index, static_cast<uint32_t>(row)};
-                        if (row + kListRows <= rows) plan->descs.push_back(item);
-                        else ragged.push_back(item);
-                    }
+                    uint64_t row = 0;
+                    for (; row + kListRows <= rows; row += kListRows)
+                        plan->descs.push_back(BlockDesc{index, static_cast<uint32_t>(row)});
+                    for (; row < rows; row += kListTailRows)
+                        ragged.push_back(BlockDesc{index, static_cast<uint32_t>(row)});
                 }
                 plan->ops.push_back(op);
             }

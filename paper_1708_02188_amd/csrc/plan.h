@@ -31,8 +31,10 @@ struct ResolvedOp {
 static_assert(sizeof(ResolvedOp) == 32, "one 32-byte scalar load per workgroup");
 
 // Work item of a phase of a several-tensor plan: rows [row, row + kListRows) of operation
-// `op` (index within the phase), a row being 64 lanes x 16 bytes.
+// `op` (index within the phase), a row being 64 lanes x 16 bytes; the rows an operation has
+// beyond a multiple of kListRows form items of kListTailRows rows.
 constexpr int kListRows = 16;
+constexpr int kListTailRows = 4;
 struct BlockDesc {
     uint32_t op;
     uint32_t row;
