@@ -328,6 +328,42 @@ def test_assignment(dev):
             assert bool((dst[:2 * G] == -1).all()) and bool((dst[2 * G + count:] == -1).all()), (dtype, count)
 
 
+def test_denormals_and_infinities_follow_ieee(dev):
+    """Subnormal operands and results are kept (no flush to zero), sums that overflow become
+    infinite, in every floating type, on both paths."""
+    dims, P, count = [2, 2], 4, 4099
+    rng = np.random.default_rng(61)
+    cases = [
+        (D.DDL_F32, np.float32, 1e-41, 3e38),
+        (D.DDL_F64, np.float64, 1e-310, 1.5e308),
+        (D.DDL_F16, np.float16, 3e-7, 6e4),
+    ]
+    for dtype, npdt, tiny, huge in cases:
+        V = [(rng.uniform(-1, 1, count) * tiny).astype(npdt) for _ in range(P)]
+        for v in V:
+            v[::7] = npdt(huge)          # some positions overflow when four are added
+            v[3::11] = npdt(0.0)
+        assert any(np.any((np.abs(v) > 0) & (np.abs(v) < np.finfo(npdt).tiny)) for v in V)
+        with np.errstate(over="ignore"):
+            want = O.allreduce_steps(V, dims)
+        assert np.isinf(want[0]).any()
+        assert np.any((np.abs(want[0]) > 0) & (np.abs(want[0]) < np.finfo(npdt).tiny))
+        plan = D.ddl_ring_plan(dims, P, count, dtype)
+        for entry in (D.ddl_allreduce_sim, D.ddl_allreduce_fused_sim):
+            bufs = upload(V, dev)
+            entry(bufs, P, plan, count, dtype)
+            for j, g in enumerate(download(bufs)):
+                assert_bitwise(g, want[j], f"{entry.__name__} dtype={dtype} learner={j}")
+    # bf16: subnormal bit patterns through the bit-level helper
+    Vb = [O.f32_to_bf16((rng.uniform(-1, 1, count) * 1e-39).astype(np.float32)) for _ in range(P)]
+    want = O.allreduce_steps(Vb, dims, add=O.bf16_add)
+    plan = D.ddl_ring_plan(dims, P, count, D.DDL_BF16)
+    bufs = upload(Vb, dev)
+    D.ddl_allreduce_sim(bufs, P, plan, count, D.DDL_BF16)
+    for j, g in enumerate(download(bufs, np.uint16)):
+        assert_bitwise(g, want[j], f"bf16 subnormals learner={j}")
+
+
 def test_buckets_on_two_streams(dev):
     """A gradient buffer cut into two buckets, each with its own plan on its own stream
     (how a framework would overlap the allreduce of early layers with later compute)."""
