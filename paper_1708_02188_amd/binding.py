@@ -92,7 +92,10 @@ class Plan:
         self.handle, self.dims, self.P, self.count, self.dtype = handle, list(dims), P, count, dtype
 
     def __del__(self):
-        ddl_plan_free(self)
+        try:
+            ddl_plan_free(self)
+        except Exception:  # interpreter shutdown: the module may already be torn down
+            pass
 
 
 def _h(plan):
