@@ -131,6 +131,26 @@ ddl_status_t ddl_allreduce_sim(void** bufs, int P, const ddl_plan_t* plan, size_
                                ddl_dtype_t dtype, void* stream);
 
 /*
+ * ddl_allreduce_sim for callers that cannot allocate device memory: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, result
+ * (bit for bit) and errors as ddl_allreduce_sim, but nothing is allocated, freed or copied
+ * from the host, not even at the plan's first use: the per-call operation records are
+ * computed on the device from the box and kept in a static device array of
+ * DDL_NOALLOC_MAX_OPS records (32 bytes each, 512 KiB, held by every GPU the library has
+ * run on until the process ends) instead of the plan's device tables.  The only set-up is
+ * the lookup of that array's address at the first call on a device (ddl_plan_prepare does
+ * it too, so call that before a capture).
+ * Limits, beyond which it returns DDL_ERR_UNSUPPORTED and enqueues nothing: P <= 256,
+ * phases * P <= DDL_NOALLOC_MAX_OPS, plans of ddl_ring_plan only (one tensor).
+ * All calls on one GPU share the array (each call rewrites the records it uses, nothing
+ * needs clearing): calls whose execution may overlap on one GPU -- different streams, or
+ * another thread -- race; order them.  ddl_allreduce_sim has no such restriction.
+ */
+#define DDL_NOALLOC_MAX_OPS 16384
+ddl_status_t ddl_allreduce_sim_noalloc(void** bufs, int P, const ddl_plan_t* plan, size_t count,
+                                       ddl_dtype_t dtype, void* stream);
+
+/*
  * The two halves as operations of their own (Sec. 4.1 ReduceScatter, AllGather); same
  * arguments and rules as ddl_allreduce_sim.
  * After ddl_reduce_scatter_sim learner r holds the completed sum on its own finest chunk

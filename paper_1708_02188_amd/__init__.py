@@ -16,7 +16,7 @@ _BINDING_NAMES = (
     "DdlError", "Plan",
     "ddl_ring_plan", "ddl_ring_plan_tensors", "ddl_plan_free", "ddl_plan_prepare",
     "ddl_plan_num_tensors", "ddl_plan_owned_chunk_tensor",
-    "ddl_assign_sim", "ddl_allreduce_sim", "ddl_reduce_scatter_sim", "ddl_allgather_sim",
+    "ddl_assign_sim", "ddl_allreduce_sim", "ddl_allreduce_sim_noalloc", "ddl_reduce_scatter_sim", "ddl_allgather_sim",
     "ddl_allreduce_sim_profile", "ddl_allreduce_sim_timed", "ddl_allreduce_fused_sim", "ddl_reduce_scatter_fused_sim", "ddl_allgather_fused_sim",
     "ddl_plan_fused_bytes",
     "ddl_plan_num_steps", "ddl_plan_num_learners", "ddl_plan_bytes_moved", "ddl_plan_step_bytes",

@@ -46,6 +46,7 @@ def _load():
         "ddl_plan_free": (None, [vp]),
         "ddl_plan_prepare": (i, [vp]),
         "ddl_allreduce_sim": (i, sim_args),
+        "ddl_allreduce_sim_noalloc": (i, sim_args),
         "ddl_reduce_scatter_sim": (i, sim_args),
         "ddl_allgather_sim": (i, sim_args),
         "ddl_assign_sim": (i, [vp, vp, sz, i, vp]),
@@ -175,6 +176,11 @@ def ddl_plan_prepare(plan):
 def ddl_allreduce_sim(bufs, P, plan, count, dtype=DDL_F32, stream=None):
     _check(_lib.ddl_allreduce_sim(_ptr_array(bufs), P, _h(plan), count, dtype, _stream(stream)),
            "ddl_allreduce_sim")
+
+
+def ddl_allreduce_sim_noalloc(bufs, P, plan, count, dtype=DDL_F32, stream=None):
+    _check(_lib.ddl_allreduce_sim_noalloc(_ptr_array(bufs), P, _h(plan), count, dtype, _stream(stream)),
+           "ddl_allreduce_sim_noalloc")
 
 
 def ddl_reduce_scatter_sim(bufs, P, plan, count, dtype=DDL_F32, stream=None):

@@ -115,9 +115,16 @@ ddl_status_t check_call(void** bufs, int P, const ddl_plan* plan, size_t count, 
         if (reinterpret_cast<uintptr_t>(bufs[j]) % 16 != 0) return DDL_ERR_ALIGN;
     }
     // learners must not share memory: sorted by address, each buffer must end before the next
-    std::vector<uintptr_t> sorted(P);
+    // (on the stack while the learners fit the kernel-argument table: no heap use then)
+    uintptr_t few[ddl::kKernargLearners];
+    std::vector<uintptr_t> many;
+    uintptr_t* sorted = few;
+    if (P > ddl::kKernargLearners) {
+        many.resize(P);
+        sorted = many.data();
+    }
     for (int j = 0; j < P; ++j) sorted[j] = reinterpret_cast<uintptr_t>(bufs[j]);
-    std::sort(sorted.begin(), sorted.end());
+    std::sort(sorted, sorted + P);
     const uintptr_t bytes = uintptr_t(count) * uintptr_t(plan->elem_size);
     for (int j = 0; j + 1 < P; ++j) {
         if (sorted[j] == sorted[j + 1]) return DDL_ERR_ARG;
@@ -253,14 +260,39 @@ bool fused_supported(const ddl_plan* plan) {
 ddl_status_t ddl_plan_prepare(const ddl_plan_t* plan) {
     if (plan == nullptr) return DDL_ERR_ARG;
     DeviceTables t;
-    if (plan->P > 1 && plan->count > 0 && fused_supported(plan)) return fused_tables(plan, &t);
-    return device_tables(plan, &t);
+    const ddl_status_t st = (plan->P > 1 && plan->count > 0 && fused_supported(plan)) ? fused_tables(plan, &t)
+                                                                                     : device_tables(plan, &t);
+    if (st != DDL_OK) return st;
+    // set-up of the allocation-free entry point: its static array's address on this device
+    ddl::ResolvedOp* records = nullptr;
+    return ddl::static_scratch(&records) == hipSuccess ? DDL_OK : DDL_ERR_HIP;
 }
 
 ddl_status_t ddl_allreduce_sim(void** bufs, int P, const ddl_plan_t* plan, size_t count,
                                ddl_dtype_t dtype, void* stream) {
     const int steps = plan ? static_cast<int>(plan->steps.size()) : 0;
     return run_steps(bufs, P, plan, count, dtype, stream, 0, steps, nullptr);
+}
+
+ddl_status_t ddl_allreduce_sim_noalloc(void** bufs, int P, const ddl_plan_t* plan, size_t count,
+                                       ddl_dtype_t dtype, void* stream_v) {
+    ddl_status_t st = check_call(bufs, P, plan, count, dtype);
+    if (st != DDL_OK) return st;
+    const size_t steps = plan->steps.size();
+    if (P > ddl::kKernargLearners || plan->seg_off.size() != 1 || steps * size_t(P) > DDL_NOALLOC_MAX_OPS)
+        return DDL_ERR_UNSUPPORTED;
+    if (count == 0 || steps == 0) return DDL_OK;
+    hipStream_t stream = static_cast<hipStream_t>(stream_v);
+    ddl::ResolvedOp* records = nullptr;
+    if (ddl::static_scratch(&records) != hipSuccess) return DDL_ERR_HIP;
+    PtrTable table;
+    std::memset(&table, 0, sizeof(table));
+    std::memcpy(table.p, bufs, size_t(P) * sizeof(void*));
+    if (ddl::launch_resolve_from_box(*plan, table, records, stream) != hipSuccess) return DDL_ERR_HIP;
+    for (size_t s = 0; s < steps; ++s)
+        if (ddl::launch_step(*plan, plan->steps[s], records + s * size_t(P), nullptr, stream) != hipSuccess)
+            return DDL_ERR_HIP;
+    return DDL_OK;
 }
 
 ddl_status_t ddl_reduce_scatter_sim(void** bufs, int P, const ddl_plan_t* plan, size_t count,

@@ -30,6 +30,11 @@
 // packed-fp32 instructions and floating-point contraction.
 #include <hip/hip_runtime.h>
 
+#include <cstring>
+#include <mutex>
+#include <utility>
+#include <vector>
+
 #include "kernels.h"
 
 #ifndef DDL_THREADS
@@ -128,6 +133,29 @@ __global__ __launch_bounds__(256) void resolve_ops(const PtrTable table, void* c
     r.reserved = 0;
     out[i] = r;
 }
+
+// The allocation-free entry point has no uploaded operation table: one thread per
+// (phase, sender) derives its transfer from the box itself and writes the record for this
+// call's buffers.
+__global__ __launch_bounds__(256) void resolve_from_box(const PtrTable table, const BoxArgs box,
+                                                        ResolvedOp* __restrict__ out) {
+    const unsigned i = blockIdx.x * 256u + threadIdx.x;
+    if (i >= box.steps * box.P) return;
+    uint64_t off, n;
+    int src, dst;
+    box_op(box, i, &off, &n, &src, &dst);
+    ResolvedOp rec;
+    rec.src = reinterpret_cast<uint64_t>(table.p[src]) + off * box.elem_size;
+    rec.dst = reinterpret_cast<uint64_t>(table.p[dst]) + off * box.elem_size;
+    rec.n = n;
+    rec.reserved = 0;
+    out[i] = rec;
+}
+
+// Operation records of the allocation-free entry point.  Every GPU the library runs on
+// holds its own copy of this array at its own address; host code uses the address that
+// hipGetSymbolAddress returns for the current device, never the array's name.
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
 typedef uint64_t u64x4 __attribute__((ext_vector_type(4)));
 
@@ -484,6 +512,44 @@ hipError_t launch_resolve(const ddl_plan& plan, const Op* d_ops, ResolvedOp* d_r
     if (total == 0) return hipSuccess;
     hipLaunchKernelGGL(resolve_ops, dim3((total + 255) / 256), dim3(256), 0, stream, table, d_ptrs,
                        d_ops, d_rops, total, static_cast<unsigned>(plan.elem_size));
+    return hipGetLastError();
+}
+
+hipError_t static_scratch(ResolvedOp** out) {
+    // the array's device address, looked up once per device with that device current
+    static std::mutex mu;
+    static std::vector<std::pair<int, void*>> known;
+    int device = -1;
+    hipError_t err = hipGetDevice(&device);
+    if (err != hipSuccess) return err;
+    std::lock_guard<std::mutex> lock(mu);
+    for (const auto& k : known)
+        if (k.first == device) {
+            *out = static_cast<ResolvedOp*>(k.second);
+            return hipSuccess;
+        }
+    void* ptr = nullptr;
+    err = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (err != hipSuccess) return err;
+    if (ptr == nullptr) return hipErrorInvalidSymbol;
+    known.emplace_back(device, ptr);
+    *out = static_cast<ResolvedOp*>(ptr);
+    return hipSuccess;
+}
+
+hipError_t launch_resolve_from_box(const ddl_plan& plan, const PtrTable& table, ResolvedOp* d_rops,
+                                   hipStream_t stream) {
+    BoxArgs box;
+    std::memset(&box, 0, sizeof(box));
+    box.m = static_cast<int32_t>(plan.dims.size());
+    for (int t = 0; t < box.m; ++t) box.dims[t] = plan.dims[t];
+    box.P = static_cast<uint32_t>(plan.P);
+    box.elem_size = static_cast<uint32_t>(plan.elem_size);
+    box.steps = static_cast<uint32_t>(plan.steps.size());
+    box.count = plan.count;
+    const unsigned total = box.steps * box.P;
+    if (total == 0) return hipSuccess;
+    hipLaunchKernelGGL(resolve_from_box, dim3((total + 255) / 256), dim3(256), 0, stream, table, box, d_rops);
     return hipGetLastError();
 }
 
