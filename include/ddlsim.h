@@ -102,12 +102,32 @@ void ddl_plan_free(ddl_plan_t* plan);
 
 /*
  * Create the plan's device tables on the current device now (those of the step-fused path
- * included, where it serves the plan), instead of at the first ddl_*_sim call that needs
- * them, which otherwise allocates once.  Call it before capturing ddl_*_sim calls into a
- * HIP graph: under capture nothing may allocate.  Capture needs P <= 256 as well (beyond
- * that every call stages the pointer array with a host-to-device copy).
+ * included, where it serves the plan) together with two free binding slots (see
+ * ddl_allreduce_sim), instead of at the first ddl_*_sim calls that need them, which
+ * otherwise allocate.  Call it before capturing ddl_*_sim calls into a HIP graph: under
+ * capture nothing may allocate.  A capture that uses the plan with more than two buffer
+ * sets reserves its slots with ddl_plan_reserve_bindings first.
  */
 ddl_status_t ddl_plan_prepare(const ddl_plan_t* plan);
+
+/* ddl_plan_prepare with at least `slots` binding slots (0 .. DDL_PLAN_MAX_BINDINGS). */
+#define DDL_PLAN_MAX_BINDINGS 64
+ddl_status_t ddl_plan_reserve_bindings(const ddl_plan_t* plan, int slots);
+
+/*
+ * How ddl_allreduce_sim enqueues the phases of a plan whose tables are already bound to
+ * the call's buffers: kernel by kernel, or as one launch of a graph recorded from those
+ * same kernels (one graph per binding slot, recorded on the current device at first need).
+ * The result is the same bit for bit; only the launch cost differs.
+ *   DDL_REPLAY_AUTO (default)  graph from a binding's second use on, for plans whose
+ *                              phases average under 16 MiB of traffic (launch-bound)
+ *   DDL_REPLAY_OFF             always kernel by kernel
+ *   DDL_REPLAY_ON              always the graph
+ * Calls made while `stream` is being captured never use it (the caller's graph already
+ * holds the kernels).
+ */
+enum { DDL_REPLAY_AUTO = 0, DDL_REPLAY_OFF = 1, DDL_REPLAY_ON = 2 };
+ddl_status_t ddl_plan_set_replay(const ddl_plan_t* plan, int mode);
 
 /*
  * In-place allreduce (Sec. 4.3: reduction R = sum_j V_j and its distribution to all
@@ -117,14 +137,23 @@ ddl_status_t ddl_plan_prepare(const ddl_plan_t* plan);
  *          owned by the caller.  The array itself may be reused as soon as the call returns.
  *          With count == 0 the pointers are not examined (empty buffers may be NULL).
  *   P, count, dtype must equal the plan's.
- * Enqueues one small kernel that binds the plan's operations to these buffers, then one
- * kernel per step, all on `stream`, and returns without synchronising; when the stream has
- * drained, every bufs[j] holds the sum, bit-identical across learners, formed in the order
- * the schedule fixes: within the ring of dimension t the partial sum of part k starts at
- * ring position k+1 and is extended by positions k+2, ..., k+d_t (= k).
- * The binding lives in the plan's device tables: calls that share a plan must be ordered
- * with respect to each other (same stream, or synchronised by the caller); use one plan
- * per stream for concurrent allreduces.
+ * Enqueues one kernel per step on `stream` and returns without synchronising; when the
+ * stream has drained, every bufs[j] holds the sum, bit-identical across learners, formed in
+ * the order the schedule fixes: within the ring of dimension t the partial sum of part k
+ * starts at ring position k+1 and is extended by positions k+2, ..., k+d_t (= k).
+ * Bindings: the kernels read absolute addresses from a per-plan table bound to one buffer
+ * set ("binding slot").  A call whose P pointers equal those of an existing slot uses it as
+ * it is; any other call binds a slot first with one more small kernel on `stream` (a free
+ * slot, else a new one, else -- with DDL_PLAN_MAX_BINDINGS slots in existence -- the least
+ * recently used).  The plan's own tables are read-only, so one plan serves any number of
+ * streams and host threads at once as long as concurrent calls use different buffer sets
+ * (they must anyway: the operation is in place) and no more than DDL_PLAN_MAX_BINDINGS
+ * sets are in flight; beyond that number a slot may be rebound while enqueued work of
+ * another stream still reads it, which the caller must then order.  Slots allocate device
+ * memory when they are created; see ddl_plan_prepare for callers that must avoid that.
+ * A call under stream capture records its own binding kernel into the caller's graph and
+ * keeps its slot for the plan's lifetime (replays stay valid whatever runs in between);
+ * if no slot is free and none can be created it returns DDL_ERR_UNSUPPORTED.
  * Errors are reported before anything is enqueued, except DDL_ERR_HIP for a failed launch.
  */
 ddl_status_t ddl_allreduce_sim(void** bufs, int P, const ddl_plan_t* plan, size_t count,

@@ -9,6 +9,7 @@ DDL_OK = 0
 DDL_ERR_ARG, DDL_ERR_DIMS, DDL_ERR_DTYPE, DDL_ERR_ALIGN = -1, -2, -3, -4
 DDL_ERR_PLAN_MISMATCH, DDL_ERR_NOMEM, DDL_ERR_HIP, DDL_ERR_UNSUPPORTED = -5, -6, -7, -8
 DDL_STEP_REDUCE, DDL_STEP_GATHER = 0, 1
+DDL_REPLAY_AUTO, DDL_REPLAY_OFF, DDL_REPLAY_ON = 0, 1, 2
 
 
 def library_path():
@@ -45,6 +46,8 @@ def _load():
         "ddl_plan_owned_chunk_tensor": (i, [vp, i, i, psz, psz]),
         "ddl_plan_free": (None, [vp]),
         "ddl_plan_prepare": (i, [vp]),
+        "ddl_plan_reserve_bindings": (i, [vp, i]),
+        "ddl_plan_set_replay": (i, [vp, i]),
         "ddl_allreduce_sim": (i, sim_args),
         "ddl_allreduce_sim_noalloc": (i, sim_args),
         "ddl_reduce_scatter_sim": (i, sim_args),
@@ -171,6 +174,14 @@ def _check(status, where):
 
 def ddl_plan_prepare(plan):
     _check(_lib.ddl_plan_prepare(_h(plan)), "ddl_plan_prepare")
+
+
+def ddl_plan_reserve_bindings(plan, slots):
+    _check(_lib.ddl_plan_reserve_bindings(_h(plan), slots), "ddl_plan_reserve_bindings")
+
+
+def ddl_plan_set_replay(plan, mode):
+    _check(_lib.ddl_plan_set_replay(_h(plan), mode), "ddl_plan_set_replay")
 
 
 def ddl_allreduce_sim(bufs, P, plan, count, dtype=DDL_F32, stream=None):

@@ -26,16 +26,24 @@ void release(T** d) {
     *d = nullptr;
 }
 
+void release_binding(ddl::Binding* b) {
+    if (b->replay) (void)hipGraphExecDestroy(static_cast<hipGraphExec_t>(b->replay));
+    release(&b->rops);
+    release(&b->d_ptrs);
+    release(&b->fused_ptrs);
+    delete b;
+}
+
 void release_tables(DeviceTables* t) {
+    for (ddl::Binding* b : t->bindings) release_binding(b);
+    t->bindings.clear();
+    if (t->capture_stream) (void)hipStreamDestroy(static_cast<hipStream_t>(t->capture_stream));
     release(&t->ops);
-    release(&t->rops);
-    release(&t->ptrs);
     release(&t->descs);
     release(&t->fused_seq);
     release(&t->fused_ctl);
     release(&t->fused_n);
     release(&t->fused_off);
-    release(&t->fused_ptrs);
 }
 
 template <typename T>
@@ -49,24 +57,24 @@ bool upload(T** d, const std::vector<T>& h) {
            hipMemcpy(*d, h.data(), h.size() * sizeof(T), hipMemcpyHostToDevice) == hipSuccess;
 }
 
-// Device copies of the step tables for the current device, created on first use.
-ddl_status_t device_tables(const ddl_plan* plan, DeviceTables* out) {
+// The plan's tables on the current device, created on first use.  Caller holds plan->mu.
+ddl_status_t device_tables_locked(const ddl_plan* plan, DeviceTables** out) {
     int device = -1;
     if (hipGetDevice(&device) != hipSuccess) return DDL_ERR_HIP;
-    std::lock_guard<std::mutex> lock(plan->mu);
-    for (const DeviceTables& t : plan->tables)
-        if (t.device == device) {
+    for (DeviceTables* t : plan->tables)
+        if (t->device == device) {
             *out = t;
             return DDL_OK;
         }
-    DeviceTables t;
-    t.device = device;
+    DeviceTables* t = new (std::nothrow) DeviceTables;
+    if (t == nullptr) return DDL_ERR_NOMEM;
+    t->device = device;
     bool ok = true;
-    if (!plan->ops.empty()) ok = upload(&t.ops, plan->ops) && reserve(&t.rops, plan->ops.size());
-    if (ok && !plan->descs.empty()) ok = upload(&t.descs, plan->descs);
-    if (ok && plan->P > ddl::kKernargLearners) ok = reserve(&t.ptrs, size_t(plan->P));
+    if (!plan->ops.empty()) ok = upload(&t->ops, plan->ops);
+    if (ok && !plan->descs.empty()) ok = upload(&t->descs, plan->descs);
     if (!ok) {
-        release_tables(&t);
+        release_tables(t);
+        delete t;
         return DDL_ERR_NOMEM;
     }
     plan->tables.push_back(t);
@@ -74,35 +82,119 @@ ddl_status_t device_tables(const ddl_plan* plan, DeviceTables* out) {
     return DDL_OK;
 }
 
-// Adds the tables of the step-fused path to the plan's entry for the current device.
-ddl_status_t fused_tables(const ddl_plan* plan, DeviceTables* out) {
-    DeviceTables base;
-    ddl_status_t st = device_tables(plan, &base);
-    if (st != DDL_OK) return st;
-    std::lock_guard<std::mutex> lock(plan->mu);
-    for (DeviceTables& t : plan->tables) {
-        if (t.device != base.device) continue;
-        if (t.fused_seq == nullptr) {
-            std::vector<uint32_t> seq, ctl;
-            int padded = 0;
-            t.fused_levels = ddl::build_fused_order(*plan, &seq, &ctl, &padded);
-            t.fused_padded = padded;
-            const bool ok = upload(&t.fused_seq, seq) && upload(&t.fused_ctl, ctl) &&
-                            upload(&t.fused_n, plan->own_n) && upload(&t.fused_off, plan->own_off) &&
-                            reserve(&t.fused_ptrs, seq.size());
-            if (!ok) {
-                release(&t.fused_seq);
-                release(&t.fused_ctl);
-                release(&t.fused_n);
-                release(&t.fused_off);
-                release(&t.fused_ptrs);
-                return DDL_ERR_NOMEM;
-            }
-        }
-        *out = t;
-        return DDL_OK;
+// Adds the tables of the step-fused path.  Caller holds plan->mu.
+ddl_status_t fused_tables_locked(const ddl_plan* plan, DeviceTables* t) {
+    if (t->fused_seq != nullptr) return DDL_OK;
+    std::vector<uint32_t> seq, ctl;
+    int padded = 0;
+    t->fused_levels = ddl::build_fused_order(*plan, &seq, &ctl, &padded);
+    t->fused_padded = padded;
+    const bool ok = upload(&t->fused_seq, seq) && upload(&t->fused_ctl, ctl) &&
+                    upload(&t->fused_n, plan->own_n) && upload(&t->fused_off, plan->own_off);
+    if (!ok) {
+        release(&t->fused_seq);
+        release(&t->fused_ctl);
+        release(&t->fused_n);
+        release(&t->fused_off);
+        return DDL_ERR_NOMEM;
     }
-    return DDL_ERR_HIP;
+    return DDL_OK;
+}
+
+bool stream_is_capturing(hipStream_t stream) {
+    hipStreamCaptureStatus status = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(stream, &status) != hipSuccess) {
+        (void)hipGetLastError();
+        return false;
+    }
+    return status != hipStreamCaptureStatusNone;
+}
+
+// Device memory of one binding slot (nothing bound yet).  Caller holds plan->mu.
+ddl::Binding* new_binding(const ddl_plan* plan, const DeviceTables* t, bool fused) {
+    ddl::Binding* b = new (std::nothrow) ddl::Binding;
+    if (b == nullptr) return nullptr;
+    bool ok = plan->ops.empty() || reserve(&b->rops, plan->ops.size());
+    if (ok && plan->P > ddl::kKernargLearners) ok = reserve(&b->d_ptrs, size_t(plan->P));
+    if (ok && fused) ok = reserve(&b->fused_ptrs, size_t(plan->P) * size_t(t->fused_padded));
+    if (!ok) {
+        release_binding(b);
+        return nullptr;
+    }
+    return b;
+}
+
+// The slot that holds this call's binding.  An eager call whose buffers are those of an
+// existing slot finds its tables bound; otherwise a slot is bound to `bufs` here: a free
+// one, a new one (never while the stream is being captured: nothing may allocate then),
+// or the least recently used.  The kernels that fill the slot's tables are enqueued on
+// `stream` before this returns.  A call under capture always records them into the graph
+// (a replay must not depend on what later eager calls did to the slot) and pins the slot.
+ddl_status_t acquire_binding(void** bufs, int P, const ddl_plan* plan, hipStream_t stream, bool fused,
+                             DeviceTables** tables_out, ddl::Binding** out, bool* was_bound) {
+    std::lock_guard<std::mutex> lock(plan->mu);
+    DeviceTables* t = nullptr;
+    ddl_status_t st = device_tables_locked(plan, &t);
+    if (st != DDL_OK) return st;
+    const bool capturing = stream_is_capturing(stream);
+    if (fused && t->fused_seq == nullptr) {
+        if (capturing) return DDL_ERR_UNSUPPORTED;  // ddl_plan_prepare was not called
+        st = fused_tables_locked(plan, t);
+        if (st != DDL_OK) return st;
+    }
+    ddl::Binding* slot = nullptr;
+    for (ddl::Binding* b : t->bindings)
+        if (b->key.size() == size_t(P) && std::memcmp(b->key.data(), bufs, size_t(P) * sizeof(void*)) == 0) {
+            slot = b;
+            break;
+        }
+    if (slot == nullptr) {
+        for (ddl::Binding* b : t->bindings)
+            if (b->key.empty()) {
+                slot = b;
+                break;
+            }
+        if (slot == nullptr && !capturing && t->bindings.size() < size_t(DDL_PLAN_MAX_BINDINGS)) {
+            slot = new_binding(plan, t, fused);
+            if (slot == nullptr) return DDL_ERR_NOMEM;
+            t->bindings.push_back(slot);
+        }
+        if (slot == nullptr) {
+            for (ddl::Binding* b : t->bindings)
+                if (!b->pinned && (slot == nullptr || b->last_use < slot->last_use)) slot = b;
+            if (slot == nullptr) return capturing ? DDL_ERR_UNSUPPORTED : DDL_ERR_NOMEM;
+        }
+        slot->key.assign(bufs, bufs + P);
+        slot->rops_valid = slot->fused_valid = false;
+        slot->uses = 0;
+    }
+    if (fused && slot->fused_ptrs == nullptr) {
+        if (capturing) return DDL_ERR_UNSUPPORTED;
+        if (!reserve(&slot->fused_ptrs, size_t(P) * size_t(t->fused_padded))) return DDL_ERR_NOMEM;
+    }
+    slot->last_use = ++t->clock;
+    const bool valid = fused ? slot->fused_valid : slot->rops_valid;
+    *was_bound = valid && !capturing;
+    if (!*was_bound) {
+        PtrTable table;
+        std::memset(&table, 0, sizeof(table));
+        void* const* d_ptrs = nullptr;
+        if (P <= ddl::kKernargLearners) {
+            std::memcpy(table.p, bufs, size_t(P) * sizeof(void*));
+        } else {
+            if (ddl::launch_store_pointers(bufs, P, slot->d_ptrs, stream) != hipSuccess) return DDL_ERR_HIP;
+            d_ptrs = slot->d_ptrs;
+        }
+        const hipError_t err = fused ? ddl::launch_fused_resolve(*plan, *t, slot->fused_ptrs, table, d_ptrs, stream)
+                                     : ddl::launch_resolve(*plan, t->ops, slot->rops, table, d_ptrs, stream);
+        if (err != hipSuccess) return DDL_ERR_HIP;
+        if (capturing) slot->pinned = true;
+        else if (fused) slot->fused_valid = true;
+        else slot->rops_valid = true;
+    }
+    *tables_out = t;
+    *out = slot;
+    return DDL_OK;
 }
 
 ddl_status_t check_call(void** bufs, int P, const ddl_plan* plan, size_t count, ddl_dtype_t dtype) {
@@ -133,47 +225,82 @@ ddl_status_t check_call(void** bufs, int P, const ddl_plan* plan, size_t count, 
     return DDL_OK;
 }
 
-// Run steps [first, last) of the plan.  events: NULL, or last-first+1 created events that
-// are recorded round every launch.  bind: first write the resolved operation table for
-// `bufs` (false only when an earlier call on the same stream has just bound them).
-ddl_status_t run_steps(void** bufs, int P, const ddl_plan* plan, size_t count, ddl_dtype_t dtype,
-                       void* stream_v, int first, int last, hipEvent_t* events, bool bind = true) {
-    ddl_status_t st = check_call(bufs, P, plan, count, dtype);
-    if (st != DDL_OK) return st;
-    hipStream_t stream = static_cast<hipStream_t>(stream_v);
-    if (count == 0 || plan->steps.empty()) return DDL_OK;
-    if (first >= last && !bind) return DDL_OK;
-
-    DeviceTables tables;
-    st = device_tables(plan, &tables);
-    if (st != DDL_OK) return st;
-
-    if (bind) {
-        PtrTable table;
-        void* const* d_ptrs = nullptr;
-        if (P <= ddl::kKernargLearners) {
-            std::memset(&table, 0, sizeof(table));
-            std::memcpy(table.p, bufs, size_t(P) * sizeof(void*));
-        } else {
-            // pageable source: the runtime has copied the array out before this returns
-            if (hipMemcpyAsync(tables.ptrs, bufs, size_t(P) * sizeof(void*), hipMemcpyHostToDevice,
-                               stream) != hipSuccess)
-                return DDL_ERR_HIP;
-            d_ptrs = tables.ptrs;
-        }
-        // bind the plan's operations to these buffers (stream-ordered before the steps)
-        if (ddl::launch_resolve(*plan, tables.ops, tables.rops, table, d_ptrs, stream) != hipSuccess)
-            return DDL_ERR_HIP;
-    }
-    if (events && hipEventRecord(events[0], stream) != hipSuccess) return DDL_ERR_HIP;
+// Enqueue the kernels of steps [first, last) for the slot's buffers.
+ddl_status_t launch_steps(const ddl_plan* plan, const DeviceTables* t, const ddl::Binding* slot, int first,
+                          int last, hipStream_t stream, hipEvent_t* events) {
+    const size_t per_step = size_t(plan->P) * plan->seg_off.size();
     for (int s = first; s < last; ++s) {
-        const size_t per_step = size_t(P) * plan->seg_off.size();
-        if (ddl::launch_step(*plan, plan->steps[s], tables.rops + size_t(s) * per_step, tables.descs,
-                             stream) != hipSuccess)
+        if (ddl::launch_step(*plan, plan->steps[s], slot->rops + size_t(s) * per_step, t->descs, stream) !=
+            hipSuccess)
             return DDL_ERR_HIP;
         if (events && hipEventRecord(events[s - first + 1], stream) != hipSuccess) return DDL_ERR_HIP;
     }
     return DDL_OK;
+}
+
+// Phases shorter than this on average are launch-bound (a phase boundary costs the GPU
+// about as long as moving this many bytes): such plans replay their phases as a graph.
+constexpr uint64_t kReplayPhaseBytes = uint64_t(16) << 20;
+
+bool wants_replay(const ddl_plan* plan, const ddl::Binding* slot) {
+    if (plan->replay_mode == DDL_REPLAY_OFF) return false;
+    if (plan->replay_mode == DDL_REPLAY_ON) return true;
+    return slot->uses >= 1 && plan->bytes_total / plan->steps.size() < kReplayPhaseBytes;
+}
+
+// The phases of the whole allreduce for one slot, recorded once as a graph.  The kernels
+// read the slot's table when they run, so the graph stays good when the slot is rebound.
+// Caller holds plan->mu.
+ddl_status_t build_replay(const ddl_plan* plan, DeviceTables* t, ddl::Binding* slot) {
+    if (t->capture_stream == nullptr) {
+        hipStream_t cs = nullptr;
+        if (hipStreamCreateWithFlags(&cs, hipStreamNonBlocking) != hipSuccess) return DDL_ERR_HIP;
+        t->capture_stream = cs;
+    }
+    hipStream_t cs = static_cast<hipStream_t>(t->capture_stream);
+    if (hipStreamBeginCapture(cs, hipStreamCaptureModeRelaxed) != hipSuccess) return DDL_ERR_HIP;
+    ddl_status_t st = launch_steps(plan, t, slot, 0, static_cast<int>(plan->steps.size()), cs, nullptr);
+    hipGraph_t graph = nullptr;
+    if (hipStreamEndCapture(cs, &graph) != hipSuccess || graph == nullptr) return DDL_ERR_HIP;
+    hipGraphExec_t exec = nullptr;
+    if (st == DDL_OK && hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0) != hipSuccess) st = DDL_ERR_HIP;
+    (void)hipGraphDestroy(graph);
+    if (st == DDL_OK) slot->replay = exec;
+    return st;
+}
+
+// Run steps [first, last) of the plan.  events: NULL, or last-first+1 created events that
+// are recorded round every launch.
+ddl_status_t run_steps(void** bufs, int P, const ddl_plan* plan, size_t count, ddl_dtype_t dtype,
+                       void* stream_v, int first, int last, hipEvent_t* events) {
+    ddl_status_t st = check_call(bufs, P, plan, count, dtype);
+    if (st != DDL_OK) return st;
+    hipStream_t stream = static_cast<hipStream_t>(stream_v);
+    if (count == 0 || plan->steps.empty()) return DDL_OK;
+
+    DeviceTables* t = nullptr;
+    ddl::Binding* slot = nullptr;
+    bool was_bound = false;
+    st = acquire_binding(bufs, P, plan, stream, false, &t, &slot, &was_bound);
+    if (st != DDL_OK) return st;
+    if (events && hipEventRecord(events[0], stream) != hipSuccess) return DDL_ERR_HIP;
+    const bool whole = first == 0 && last == static_cast<int>(plan->steps.size()) && events == nullptr;
+    if (whole && !stream_is_capturing(stream)) {
+        hipGraphExec_t exec = nullptr;
+        {
+            std::lock_guard<std::mutex> lock(plan->mu);
+            if (wants_replay(plan, slot)) {
+                if (slot->replay == nullptr) {
+                    st = build_replay(plan, t, slot);
+                    if (st != DDL_OK) return st;
+                }
+                exec = static_cast<hipGraphExec_t>(slot->replay);
+            }
+            if (was_bound) ++slot->uses;
+        }
+        if (exec != nullptr) return hipGraphLaunch(exec, stream) == hipSuccess ? DDL_OK : DDL_ERR_HIP;
+    }
+    return launch_steps(plan, t, slot, first, last, stream, events);
 }
 
 ddl_plan_t* make_plan(const int* dims, int m, int P, const size_t* seg_off, const size_t* seg_count,
@@ -242,7 +369,10 @@ ddl_plan_t* ddl_ring_plan_tensors(const int* dims, int m, int P, const size_t* t
 
 void ddl_plan_free(ddl_plan_t* plan) {
     if (plan == nullptr) return;
-    for (DeviceTables& t : plan->tables) release_tables(&t);
+    for (DeviceTables* t : plan->tables) {
+        release_tables(t);
+        delete t;
+    }
     delete plan;
 }
 
@@ -255,17 +385,45 @@ bool fused_supported(const ddl_plan* plan) {
     return plan->P <= DDL_FUSED_MAX_LEARNERS && levels <= DDL_FUSED_MAX_LEVELS && plan->seg_off.size() == 1;
 }
 
-}  // namespace
-
-ddl_status_t ddl_plan_prepare(const ddl_plan_t* plan) {
-    if (plan == nullptr) return DDL_ERR_ARG;
-    DeviceTables t;
-    const ddl_status_t st = (plan->P > 1 && plan->count > 0 && fused_supported(plan)) ? fused_tables(plan, &t)
-                                                                                     : device_tables(plan, &t);
-    if (st != DDL_OK) return st;
+// Tables on the current device plus at least `slots` binding slots.
+ddl_status_t prepare(const ddl_plan* plan, int slots) {
+    if (plan == nullptr || slots < 0 || slots > DDL_PLAN_MAX_BINDINGS) return DDL_ERR_ARG;
+    {
+        std::lock_guard<std::mutex> lock(plan->mu);
+        DeviceTables* t = nullptr;
+        ddl_status_t st = device_tables_locked(plan, &t);
+        if (st != DDL_OK) return st;
+        const bool fused = plan->P > 1 && plan->count > 0 && fused_supported(plan);
+        if (fused) {
+            st = fused_tables_locked(plan, t);
+            if (st != DDL_OK) return st;
+        }
+        for (ddl::Binding* b : t->bindings)
+            if (fused && b->fused_ptrs == nullptr &&
+                !reserve(&b->fused_ptrs, size_t(plan->P) * size_t(t->fused_padded)))
+                return DDL_ERR_NOMEM;
+        while (t->bindings.size() < size_t(slots)) {
+            ddl::Binding* b = new_binding(plan, t, fused);
+            if (b == nullptr) return DDL_ERR_NOMEM;
+            t->bindings.push_back(b);
+        }
+    }
     // set-up of the allocation-free entry point: its static array's address on this device
     ddl::ResolvedOp* records = nullptr;
     return ddl::static_scratch(&records) == hipSuccess ? DDL_OK : DDL_ERR_HIP;
+}
+
+}  // namespace
+
+ddl_status_t ddl_plan_prepare(const ddl_plan_t* plan) { return prepare(plan, 2); }
+
+ddl_status_t ddl_plan_reserve_bindings(const ddl_plan_t* plan, int slots) { return prepare(plan, slots); }
+
+ddl_status_t ddl_plan_set_replay(const ddl_plan_t* plan, int mode) {
+    if (plan == nullptr || mode < DDL_REPLAY_AUTO || mode > DDL_REPLAY_ON) return DDL_ERR_ARG;
+    std::lock_guard<std::mutex> lock(plan->mu);
+    plan->replay_mode = mode;
+    return DDL_OK;
 }
 
 ddl_status_t ddl_allreduce_sim(void** bufs, int P, const ddl_plan_t* plan, size_t count,
@@ -318,26 +476,15 @@ ddl_status_t run_fused(void** bufs, int P, const ddl_plan* plan, size_t count, d
     if (!fused_supported(plan)) return DDL_ERR_UNSUPPORTED;
     if (count == 0 || P == 1) return DDL_OK;
     hipStream_t stream = static_cast<hipStream_t>(stream_v);
-    DeviceTables t;
-    st = fused_tables(plan, &t);
+    DeviceTables* t = nullptr;
+    ddl::Binding* slot = nullptr;
+    bool was_bound = false;
+    st = acquire_binding(bufs, P, plan, stream, true, &t, &slot, &was_bound);
     if (st != DDL_OK) return st;
-    PtrTable table;
-    void* const* d_ptrs = nullptr;
-    if (P <= ddl::kKernargLearners) {
-        std::memset(&table, 0, sizeof(table));
-        std::memcpy(table.p, bufs, size_t(P) * sizeof(void*));
-    } else {
-        if (hipMemcpyAsync(t.ptrs, bufs, size_t(P) * sizeof(void*), hipMemcpyHostToDevice, stream) !=
-            hipSuccess)
-            return DDL_ERR_HIP;
-        d_ptrs = t.ptrs;
-    }
-    if (ddl::launch_fused_resolve(*plan, t, t.fused_padded, t.fused_off, table, d_ptrs, stream) != hipSuccess)
-        return DDL_ERR_HIP;
     uint64_t max_chunk = 0;
     for (uint64_t n : plan->own_n) max_chunk = n > max_chunk ? n : max_chunk;
     auto pass = [&](int mode) {
-        return ddl::launch_fused(*plan, t, t.fused_padded, t.fused_levels, max_chunk, mode, stream) == hipSuccess;
+        return ddl::launch_fused(*plan, *t, slot->fused_ptrs, max_chunk, mode, stream) == hipSuccess;
     };
     // Measured on MI355X: from about 32 learners on, two passes (all reads of the reduction
     // first, then all writes of the distribution) sustain more bandwidth than one pass that
@@ -419,14 +566,12 @@ ddl_status_t ddl_allreduce_sim_timed(void** bufs, int P, const ddl_plan_t* plan,
     hipEvent_t ev[3] = {nullptr, nullptr, nullptr};
     for (int i = 0; i < 3 && st == DDL_OK; ++i)
         if (hipEventCreate(&ev[i]) != hipSuccess) st = DDL_ERR_HIP;
-    // bind first (untimed), then the two halves between events
-    if (st == DDL_OK) st = run_steps(bufs, P, plan, count, dtype, stream, 0, 0, nullptr, true);
+    // bind first (untimed: an empty range of steps), then the two halves between events
+    if (st == DDL_OK) st = run_steps(bufs, P, plan, count, dtype, stream, 0, 0, nullptr);
     if (st == DDL_OK && hipEventRecord(ev[0], hs) != hipSuccess) st = DDL_ERR_HIP;
-    if (st == DDL_OK)
-        st = run_steps(bufs, P, plan, count, dtype, stream, 0, plan->first_gather, nullptr, false);
+    if (st == DDL_OK) st = run_steps(bufs, P, plan, count, dtype, stream, 0, plan->first_gather, nullptr);
     if (st == DDL_OK && hipEventRecord(ev[1], hs) != hipSuccess) st = DDL_ERR_HIP;
-    if (st == DDL_OK)
-        st = run_steps(bufs, P, plan, count, dtype, stream, plan->first_gather, steps, nullptr, false);
+    if (st == DDL_OK) st = run_steps(bufs, P, plan, count, dtype, stream, plan->first_gather, steps, nullptr);
     if (st == DDL_OK && hipEventRecord(ev[2], hs) != hipSuccess) st = DDL_ERR_HIP;
     if (hipStreamSynchronize(hs) != hipSuccess && st == DDL_OK) st = DDL_ERR_HIP;
     float ms = 0.0f;

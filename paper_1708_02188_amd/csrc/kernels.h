@@ -105,15 +105,18 @@ hipError_t launch_step(const ddl_plan& plan, const Step& step, const ResolvedOp*
 // Plain copy of n elements with the all-gather phase's streaming shape.
 hipError_t launch_assign(ddl_dtype_t dtype, void* dst, const void* src, uint64_t n, hipStream_t stream);
 
+// Copy the P learner pointers of the host array `bufs` into the device array d_ptrs, through
+// kernel arguments (kKernargLearners per launch); `bufs` is not referenced after return.
+hipError_t launch_store_pointers(void* const* bufs, int P, void** d_ptrs, hipStream_t stream);
+
 // Step-fused allreduce.  launch_fused_resolve binds the summation-order table to the
-// caller's buffers: d_ptrs_out[c * padded + i] = address of finest chunk c in learner
-// seq[c][i].  launch_fused runs the single pass over all chunks.
-hipError_t launch_fused_resolve(const ddl_plan& plan, const DeviceTables& t, int padded,
-                                const uint64_t* d_own_off, const PtrTable& table,
-                                void* const* d_ptrs, hipStream_t stream);
+// caller's buffers: fused_ptrs[c * padded + i] = address of finest chunk c in learner
+// seq[c][i].  launch_fused runs one pass over all chunks.
+hipError_t launch_fused_resolve(const ddl_plan& plan, const DeviceTables& t, uint64_t* fused_ptrs,
+                                const PtrTable& table, void* const* d_ptrs, hipStream_t stream);
 // mode: 0 = fold and store to all learners, 1 = fold and store to the chunk's owner,
 // 2 = copy the owner's chunk to all other learners.
-hipError_t launch_fused(const ddl_plan& plan, const DeviceTables& t, int padded, int levels,
+hipError_t launch_fused(const ddl_plan& plan, const DeviceTables& t, const uint64_t* fused_ptrs,
                         uint64_t max_chunk, int mode, hipStream_t stream);
 
 }  // namespace ddl

@@ -116,6 +116,14 @@ template <typename V> __device__ __forceinline__ void stream_store(DDL_GLOBAL V*
 #endif
 }
 
+// Learner pointers beyond what one kernel-argument table holds reach the device in slices
+// of that table, so that no call ever reads the caller's host array asynchronously.
+__global__ __launch_bounds__(256) void store_pointers(const PtrTable slice, void** __restrict__ d_ptrs,
+                                                      unsigned first, unsigned P) {
+    const unsigned j = first + threadIdx.x;
+    if (threadIdx.x < unsigned(kKernargLearners) && j < P) d_ptrs[j] = slice.p[threadIdx.x];
+}
+
 // One thread per (step, sender): absolute addresses for this call's buffers.
 __global__ __launch_bounds__(256) void resolve_ops(const PtrTable table, void* const* __restrict__ d_ptrs,
                                                    const Op* __restrict__ ops, ResolvedOp* __restrict__ out,
@@ -480,31 +488,45 @@ __global__ __launch_bounds__(64) void fused_gather_kernel(const uint64_t* ptrs_,
 }
 
 template <typename T>
-hipError_t launch_fused_typed(const ddl_plan& plan, const DeviceTables& t, int padded, int levels,
-                              uint64_t max_chunk, int mode, hipStream_t stream) {
+hipError_t launch_fused_typed(const ddl_plan& plan, const DeviceTables& t, const uint64_t* fused_ptrs,
+                              int padded, int levels, uint64_t max_chunk, int mode, hipStream_t stream) {
     constexpr uint64_t VL = 16 / sizeof(typename Elem<T>::S);
     uint64_t tiles = (max_chunk / VL + 1 + (kRowVecs - 1) + 63) / 64;
     const uint64_t max_x = ((uint64_t(1) << 32) / 64 - 1) / uint64_t(plan.P);
     if (tiles > max_x) tiles = max_x;
     const dim3 grid(static_cast<unsigned>(tiles), static_cast<unsigned>(plan.P), 1);
     if (mode == FUSED_ALL)
-        hipLaunchKernelGGL((fused_kernel<T, FUSED_ALL>), grid, dim3(64), 0, stream, t.fused_ptrs,
+        hipLaunchKernelGGL((fused_kernel<T, FUSED_ALL>), grid, dim3(64), 0, stream, fused_ptrs,
                            t.fused_ctl, t.fused_n, plan.P, padded, levels, grid.x);
     else if (mode == FUSED_REDUCE)
-        hipLaunchKernelGGL((fused_kernel<T, FUSED_REDUCE>), grid, dim3(64), 0, stream, t.fused_ptrs,
+        hipLaunchKernelGGL((fused_kernel<T, FUSED_REDUCE>), grid, dim3(64), 0, stream, fused_ptrs,
                            t.fused_ctl, t.fused_n, plan.P, padded, levels, grid.x);
     else {
         const unsigned groups = static_cast<unsigned>((plan.P - 1 + DDL_GATHER_GROUP - 1) / DDL_GATHER_GROUP);
         const uint64_t max_x3 = ((uint64_t(1) << 32) / 64 - 1) / (uint64_t(plan.P) * groups);
         const unsigned x = static_cast<unsigned>(tiles > max_x3 ? max_x3 : tiles);
         const dim3 grid3(x ? x : 1, groups, static_cast<unsigned>(plan.P));
-        hipLaunchKernelGGL((fused_gather_kernel<T>), grid3, dim3(64), 0, stream, t.fused_ptrs, t.fused_n,
+        hipLaunchKernelGGL((fused_gather_kernel<T>), grid3, dim3(64), 0, stream, fused_ptrs, t.fused_n,
                            plan.P, padded, grid3.x);
     }
     return hipGetLastError();
 }
 
 }  // namespace
+
+hipError_t launch_store_pointers(void* const* bufs, int P, void** d_ptrs, hipStream_t stream) {
+    for (int first = 0; first < P; first += kKernargLearners) {
+        PtrTable slice;
+        std::memset(&slice, 0, sizeof(slice));
+        const int now = P - first < kKernargLearners ? P - first : kKernargLearners;
+        std::memcpy(slice.p, bufs + first, size_t(now) * sizeof(void*));
+        hipLaunchKernelGGL(store_pointers, dim3(1), dim3(256), 0, stream, slice, d_ptrs, unsigned(first),
+                           unsigned(P));
+        const hipError_t err = hipGetLastError();
+        if (err != hipSuccess) return err;
+    }
+    return hipSuccess;
+}
 
 hipError_t launch_resolve(const ddl_plan& plan, const Op* d_ops, ResolvedOp* d_rops,
                           const PtrTable& table, void* const* d_ptrs, hipStream_t stream) {
@@ -588,24 +610,25 @@ hipError_t launch_assign(ddl_dtype_t dtype, void* dst, const void* src, uint64_t
     return hipErrorInvalidValue;
 }
 
-hipError_t launch_fused_resolve(const ddl_plan& plan, const DeviceTables& t, int padded,
-                                const uint64_t* d_own_off, const PtrTable& table,
-                                void* const* d_ptrs, hipStream_t stream) {
+hipError_t launch_fused_resolve(const ddl_plan& plan, const DeviceTables& t, uint64_t* fused_ptrs,
+                                const PtrTable& table, void* const* d_ptrs, hipStream_t stream) {
+    const int padded = t.fused_padded;
     const unsigned total = unsigned(plan.P) * unsigned(padded);
     hipLaunchKernelGGL(fused_resolve, dim3((total + 255) / 256), dim3(256), 0, stream, table, d_ptrs,
-                       t.fused_seq, d_own_off, t.fused_ptrs, unsigned(plan.P), unsigned(padded),
+                       t.fused_seq, t.fused_off, fused_ptrs, unsigned(plan.P), unsigned(padded),
                        unsigned(plan.elem_size));
     return hipGetLastError();
 }
 
-hipError_t launch_fused(const ddl_plan& plan, const DeviceTables& t, int padded, int levels,
+hipError_t launch_fused(const ddl_plan& plan, const DeviceTables& t, const uint64_t* fused_ptrs,
                         uint64_t max_chunk, int mode, hipStream_t stream) {
+    const int padded = t.fused_padded, levels = t.fused_levels;
     switch (plan.dtype) {
-        case DDL_F32: return launch_fused_typed<float>(plan, t, padded, levels, max_chunk, mode, stream);
-        case DDL_F64: return launch_fused_typed<double>(plan, t, padded, levels, max_chunk, mode, stream);
-        case DDL_I32: return launch_fused_typed<unsigned>(plan, t, padded, levels, max_chunk, mode, stream);
-        case DDL_F16: return launch_fused_typed<_Float16>(plan, t, padded, levels, max_chunk, mode, stream);
-        case DDL_BF16: return launch_fused_typed<bf16_bits>(plan, t, padded, levels, max_chunk, mode, stream);
+        case DDL_F32: return launch_fused_typed<float>(plan, t, fused_ptrs, padded, levels, max_chunk, mode, stream);
+        case DDL_F64: return launch_fused_typed<double>(plan, t, fused_ptrs, padded, levels, max_chunk, mode, stream);
+        case DDL_I32: return launch_fused_typed<unsigned>(plan, t, fused_ptrs, padded, levels, max_chunk, mode, stream);
+        case DDL_F16: return launch_fused_typed<_Float16>(plan, t, fused_ptrs, padded, levels, max_chunk, mode, stream);
+        case DDL_BF16: return launch_fused_typed<bf16_bits>(plan, t, fused_ptrs, padded, levels, max_chunk, mode, stream);
     }
     return hipErrorInvalidValue;
 }

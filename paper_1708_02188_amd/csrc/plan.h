@@ -60,11 +60,26 @@ struct Step {
 constexpr int kFusedBatch = DDL_FUSED_BATCH;
 constexpr uint32_t kFusedValid = 0x80000000u;
 
+// A plan's operations bound to one set of learner buffers on one device.  The phase kernels
+// read absolute addresses from `rops`; a call whose buffers equal `key` finds them there
+// and binds nothing.  Slots are bound by the calls themselves (least recently used first
+// once DDL_PLAN_MAX_BINDINGS exist).
+struct Binding {
+    std::vector<void*> key;           // the P learner pointers (empty: never bound)
+    ResolvedOp* rops = nullptr;       // the plan's operations for these buffers, step-major
+    void** d_ptrs = nullptr;          // the pointers on the device, when P exceeds the kernarg table
+    uint64_t* fused_ptrs = nullptr;   // step-fused path: P * padded absolute addresses (on demand)
+    bool rops_valid = false;          // an eager call has enqueued the kernel that fills rops for `key`
+    bool fused_valid = false;         // the same for fused_ptrs
+    bool pinned = false;              // a captured graph refers to this slot: it is never rebound
+    uint64_t last_use = 0;
+    uint64_t uses = 0;                // eager whole-allreduce calls that found the slot bound
+    void* replay = nullptr;           // hipGraphExec_t: the phases of the whole allreduce as one graph
+};
+
 struct DeviceTables {
     int device = -1;
     Op* ops = nullptr;           // num_steps * P operations, step-major
-    ResolvedOp* rops = nullptr;  // the same operations bound to the buffers of the latest call
-    void** ptrs = nullptr;       // staging for the learner pointers when P exceeds the kernarg table
     BlockDesc* descs = nullptr;  // work list of a several-tensor plan
     // step-fused path, created at its first use
     uint32_t* fused_seq = nullptr;    // P * padded learner ranks
@@ -73,7 +88,9 @@ struct DeviceTables {
     uint64_t* fused_off = nullptr;    // element offset of each finest chunk
     int fused_levels = 0;             // box dimensions of size > 1
     int fused_padded = 0;             // row length of fused_seq / fused_ptrs
-    uint64_t* fused_ptrs = nullptr;   // P * padded absolute addresses, bound per call
+    std::vector<Binding*> bindings;
+    uint64_t clock = 0;               // orders the bindings' last uses
+    void* capture_stream = nullptr;   // hipStream_t on which replay graphs are recorded
 };
 
 }  // namespace ddl
@@ -92,8 +109,9 @@ struct ddl_plan {
     std::vector<uint64_t> own_off, own_n; // finest chunk per (tensor, learner)
     uint64_t bytes_total = 0;
 
-    mutable std::mutex mu;                      // guards `tables`
-    mutable std::vector<ddl::DeviceTables> tables;  // one entry per device the plan ran on
+    mutable std::mutex mu;                       // guards `tables` and everything below them
+    mutable std::vector<ddl::DeviceTables*> tables;  // one entry per device the plan ran on
+    mutable int replay_mode = 0;                 // DDL_REPLAY_AUTO / _OFF / _ON
 };
 
 namespace ddl {

@@ -390,6 +390,114 @@ def test_buckets_on_two_streams(dev):
         assert_bitwise(g[cut:], want_b[j], f"bucket 1 learner={j}")
 
 
+def test_one_plan_two_streams_disjoint_buffer_sets(dev):
+    """The plan's tables are read-only; every buffer set has its own binding slot, so one
+    plan serves two streams at once on disjoint buffers."""
+    dims, P, count = [4, 4], 16, 1_000_003
+    rng = np.random.default_rng(66)
+    VA = wide_inputs(rng, P, count, D.DDL_F32)
+    VB = wide_inputs(rng, P, count, D.DDL_F32)
+    want_a = O.allreduce_steps(O.allreduce_steps(VA, dims), dims)
+    want_b = O.allreduce_steps(O.allreduce_steps(VB, dims), dims)
+    plan = D.ddl_ring_plan(dims, P, count)
+    A, B = upload(VA, dev), upload(VB, dev)
+    sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+    say("one plan, two streams, interleaved calls")
+    for _ in range(2):
+        D.ddl_allreduce_sim(A, P, plan, count, D.DDL_F32, sa)
+        D.ddl_allreduce_sim(B, P, plan, count, D.DDL_F32, sb)
+    sa.synchronize()
+    sb.synchronize()
+    for j in range(P):
+        assert_bitwise(A[j].cpu().numpy(), want_a[j], f"stream a learner={j}")
+        assert_bitwise(B[j].cpu().numpy(), want_b[j], f"stream b learner={j}")
+    # the fused path keeps its binding per buffer set as well
+    A, B = upload(VA, dev), upload(VB, dev)
+    torch.cuda.synchronize()
+    D.ddl_allreduce_fused_sim(A, P, plan, count, D.DDL_F32, sa)
+    D.ddl_allreduce_fused_sim(B, P, plan, count, D.DDL_F32, sb)
+    sa.synchronize()
+    sb.synchronize()
+    fold_a, fold_b = O.allreduce_fold(VA, dims), O.allreduce_fold(VB, dims)
+    for j in range(P):
+        assert_bitwise(A[j].cpu().numpy(), fold_a, f"fused stream a learner={j}")
+        assert_bitwise(B[j].cpu().numpy(), fold_b, f"fused stream b learner={j}")
+
+
+def test_more_buffer_sets_than_binding_slots(dev):
+    """Slots are rebound, least recently used first, once the plan holds its maximum."""
+    dims, P, count = [2, 2], 4, 5003
+    plan = D.ddl_ring_plan(dims, P, count)
+    rng = np.random.default_rng(12)
+    sets, wants = [], []
+    for i in range(70):  # more than DDL_PLAN_MAX_BINDINGS = 64
+        V = [rng.uniform(-1, 1, count).astype(np.float32) for _ in range(P)]
+        sets.append(upload(V, dev))
+        wants.append(O.allreduce_fold(V, dims))
+    for bufs in sets:
+        D.ddl_allreduce_sim(bufs, P, plan, count)
+    for bufs in sets[:3]:   # evicted by now: bound again; and a second pass over the same set
+        D.ddl_allreduce_sim(bufs, P, plan, count)
+    torch.cuda.synchronize()
+    for i, bufs in enumerate(sets):
+        want = wants[i] if i >= 3 else O.allreduce_fold([wants[i]] * P, dims)
+        for j in range(P):
+            assert_bitwise(bufs[j].cpu().numpy(), want, f"set {i} learner={j}")
+    with pytest.raises(D.DdlError) as e:
+        D.ddl_plan_reserve_bindings(plan, 65)
+    assert e.value.status == D.DDL_ERR_ARG
+
+
+@pytest.mark.parametrize("mode", ["auto", "on", "off"])
+def test_graph_replay_of_the_phases_gives_the_same_bits(dev, mode):
+    """Launch-bound plans replay their phases as one graph per binding slot; repeated calls,
+    alternating buffer sets and eager work in between must all give the eager result."""
+    dims, P, count = [4, 2, 2], 16, 20011
+    rng = np.random.default_rng(91)
+    plan = D.ddl_ring_plan(dims, P, count)
+    D.ddl_plan_set_replay(plan, {"auto": D.DDL_REPLAY_AUTO, "on": D.DDL_REPLAY_ON, "off": D.DDL_REPLAY_OFF}[mode])
+    Vs = [[(rng.uniform(-1, 1, count) * 1e-3).astype(np.float32) for _ in range(P)] for _ in range(2)]
+    sets = [upload(V, dev) for V in Vs]
+    want = [[v.copy() for v in V] for V in Vs]
+    stream = torch.cuda.current_stream()
+    for call in range(6):
+        k = call % 2 if call < 4 else 0
+        say(f"replay mode {mode}: call {call} on set {k}")
+        D.ddl_allreduce_sim(sets[k], P, plan, count, D.DDL_F32, stream)
+        want[k] = O.allreduce_steps(want[k], dims)
+        for j, g in enumerate(download(sets[k])):
+            assert_bitwise(g, want[k][j], f"mode {mode} call {call} learner={j}")
+        sets[k][0].add_(0.0)   # eager work between the calls
+    with pytest.raises(D.DdlError):
+        D.ddl_plan_set_replay(plan, 7)
+
+
+def test_capture_with_more_learners_than_the_kernarg_table(dev):
+    """Beyond 256 learners the pointers reach the device through kernel arguments too, so
+    such a call can be captured; the replay binds its slot itself."""
+    dims, count, P = [8, 8, 8], 4099, 512
+    V = [I.fill_host(count, 11, j, "uniform") for j in range(P)]
+    want = O.allreduce_fold(V, dims)
+    plan = D.ddl_ring_plan(dims, P, count)
+    D.ddl_plan_prepare(plan)
+    bufs = upload(V, dev)
+    other = [torch.zeros(count, dtype=torch.float32, device=dev) for _ in range(P)]
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    torch.cuda.synchronize()
+    with torch.cuda.graph(graph, stream=side):
+        D.ddl_allreduce_sim(bufs, P, plan, count, D.DDL_F32, torch.cuda.current_stream())
+    for replay in range(3):
+        D.ddl_allreduce_sim(other, P, plan, count)      # eager call on another set in between
+        for b, v in zip(bufs, V):
+            b.copy_(torch.from_numpy(v))
+        torch.cuda.synchronize()
+        graph.replay()
+        for j, g in enumerate(download(bufs)):
+            assert_bitwise(g, want, f"P=512 replay {replay} learner={j}")
+
+
 def test_buffers_as_aligned_views_of_one_allocation(dev):
     dims, count, P = [2, 2], 10007, 4
     stride = 10240  # elements; multiple of 4 -> 16-byte aligned views, non-overlapping
