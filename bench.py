@@ -2,17 +2,24 @@
 """Benchmark of the simulated multi-ring allreduce on one MI355X.
 
 A step is one whole allreduce (every reduce-scatter and all-gather phase of the schedule)
-over one set of P synthetic learner buffers that is already resident in HBM.  Prints ONE
-JSON line: allreduce GB/s per virtual learner (`value`), the HBM roofline of the dominant
-kernel measured with HIP events round every phase, and the CPU oracle timed on the host.
+over one set of P synthetic learner buffers that is already resident in HBM.  Every step
+runs between its own pair of HIP events on the stream the kernels are launched on; the
+buffers are refilled from the seeded generator before every step, outside the events, so
+every step sums fresh N(0, 1e-2) or uniform data and nothing overflows.  Prints ONE JSON
+line: allreduce GB/s per virtual learner (`value`, from the median step), the HBM roofline
+of the dominant kernel, the other configurations as secondary entries, and the CPU oracle
+timed on the host.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2] [--no-cpu]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 5] [--no-cpu]
+    python bench.py --dims 4,8 --count 1000000 --dist uniform --seed 7     # ad-hoc shape
 """
 import argparse
 import json
 import os
+import statistics
 import sys
 import time
+from math import prod
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
@@ -20,47 +27,256 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 
+# HBM bytes per launch of the dominant kernel from rocprofv3 counter runs (FETCH_SIZE and
+# WRITE_SIZE, each in a run of its own, scaled by the same counters' reading for a plain
+# copy of known size).  Recorded figures, not measured by this program: a counter run needs
+# the profiler around the process.  The summaries that hold them are named beside them.
+RECORDED_TRAFFIC = {
+}
 
-def box_sweep(torch, D, dev, P=256, iters=30):
+
+def time_calls(torch, stream, call, refill, K, W):
+    """W untimed calls, then K calls each between its own event pair on `stream`;
+    refill(i) runs before call(i), outside the events.  Returns the K times in ms and the
+    wall-clock seconds of the timed loop (refills included)."""
+    for i in range(W):
+        refill(i)
+        call(i)
+    torch.cuda.synchronize()
+    pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(K)]
+    t0 = time.perf_counter()
+    for i in range(K):
+        refill(W + i)
+        pairs[i][0].record(stream)
+        call(W + i)
+        pairs[i][1].record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    return [a.elapsed_time(b) for a, b in pairs], wall
+
+
+def rate(nbytes, ms):
+    gbs = nbytes / (ms * 1e-3) / 1e9
+    return gbs, gbs / HBM_PEAK_GBS
+
+
+class Workload:
+    """One configuration resident on the device: `n_sets` sets of P learner buffers."""
+
+    stagger_bytes = 0   # learner j's buffer starts (j % 4) * stagger_bytes into its allocation
+
+    def __init__(self, torch, D, I, dev, cfg, n_sets):
+        self.torch, self.D, self.I, self.cfg = torch, D, I, cfg
+        self.P, self.dims, self.count = cfg["P"], cfg["dims"], cfg["count"]
+        self.dist, self.seed = cfg["dist"], cfg["seed"]
+        self.stream = torch.cuda.current_stream()
+        pad = self.stagger_bytes // 4
+        self.sets = [[torch.empty(self.count + 3 * pad, dtype=torch.float32, device=dev)[(j % 4) * pad:][:self.count]
+                      for j in range(self.P)] for _ in range(n_sets)]
+        # pointer arrays are built once: the timed calls marshal nothing
+        self.ptrs = [D.pointer_array(s) for s in self.sets]
+        self.plan = D.ddl_ring_plan(self.dims, self.P, self.count)
+        D.ddl_plan_prepare(self.plan)
+
+    def refill(self, i):
+        bufs = self.sets[i % len(self.sets)]
+        for j, b in enumerate(bufs):
+            self.I.fill_device(b, self.seed + 1000 * i, j, self.dist, 0, self.stream)
+
+    def entry(self, fn, plan=None):
+        plan = plan or self.plan
+        return lambda i: fn(self.ptrs[i % len(self.sets)], self.P, plan, self.count, self.D.DDL_F32, self.stream)
+
+    def measure(self, fn, K, W, plan=None, nbytes=None):
+        ms, wall = time_calls(self.torch, self.stream, self.entry(fn, plan), self.refill, K, W)
+        med = statistics.median(ms)
+        out = {"ms_per_step": med, "ms_mean": statistics.fmean(ms), "ms_min": min(ms), "ms_max": max(ms),
+               "GBs_per_virtual_learner": 4 * self.count / (med * 1e-3) / 1e9,
+               "wall_s_with_refills": round(wall, 4)}
+        if nbytes:
+            out["bytes"] = nbytes
+            out["achieved_GBs"], out["frac"] = rate(nbytes, med)
+        return out
+
+    def identical(self, i):
+        last = self.sets[i % len(self.sets)]
+        t = self.torch
+        return all(t.equal(last[0].view(t.int32), last[j].view(t.int32)) for j in range(1, self.P))
+
+    def tensor_plan(self):
+        I = self.I
+        shapes = I.resnet50_shapes() if self.count == I.RESNET50_COUNT else (
+            I.resnet101_22k_shapes() if self.count == I.RESNET101_22K_COUNT else None)
+        if shapes is None:
+            return None, 0
+        offs, cnts = I.tensor_segments(shapes)
+        tplan = self.D.ddl_ring_plan_tensors(self.dims, self.P, offs, cnts, self.count)
+        self.D.ddl_plan_prepare(tplan)
+        return tplan, len(offs)
+
+    def close(self):
+        self.sets, self.ptrs, self.plan = [], [], None
+        self.torch.cuda.empty_cache()
+
+
+def kernel_roofline(w, passes):
+    """Average launch duration of the reduce-add and copy kernels: one event pair round each
+    half of the allreduce, so gaps between the launches are in, event overhead is not."""
+    D = w.D
+    nsteps = D.ddl_plan_num_steps(w.plan)
+    kinds = [D.ddl_plan_get_step(w.plan, s)[0] for s in range(nsteps)]
+    step_bytes = [D.ddl_plan_step_bytes(w.plan, s) for s in range(nsteps)]
+    acc_ms = {D.DDL_STEP_REDUCE: 0.0, D.DDL_STEP_GATHER: 0.0}
+    acc_bytes = {D.DDL_STEP_REDUCE: 0, D.DDL_STEP_GATHER: 0}
+    launches = {D.DDL_STEP_REDUCE: 0, D.DDL_STEP_GATHER: 0}
+    for p in range(passes):
+        w.refill(7000 + p)
+        r_ms, g_ms = D.ddl_allreduce_sim_timed(w.ptrs[(7000 + p) % len(w.sets)], w.P, w.plan, w.count,
+                                               D.DDL_F32, w.stream)
+        acc_ms[D.DDL_STEP_REDUCE] += r_ms
+        acc_ms[D.DDL_STEP_GATHER] += g_ms
+        for s in range(nsteps):
+            if step_bytes[s]:
+                acc_bytes[kinds[s]] += step_bytes[s]
+                launches[kinds[s]] += 1
+
+    def line(kind, name):
+        if not launches[kind]:
+            return None
+        gbs = acc_bytes[kind] / (acc_ms[kind] * 1e-3) / 1e9
+        return {"kernel": name, "launches": launches[kind], "avg_launch_us": 1e3 * acc_ms[kind] / launches[kind],
+                "avg_launch_bytes": acc_bytes[kind] / launches[kind], "achieved_GBs": gbs,
+                "frac": gbs / HBM_PEAK_GBS}
+
+    return (line(D.DDL_STEP_REDUCE, "reduce_add_step (step_kernel<float,true>)"),
+            line(D.DDL_STEP_GATHER, "copy_step (step_kernel<float,false>)"))
+
+
+def secondary(torch, D, I, dev, cfg, K, W, budget_bytes):
+    """A configuration other than the headline one: the schedule, the step-fused variant and,
+    where the buffer is a layer list, the per-tensor variant; small ones also under graph
+    replay of the phases."""
+    resident = 4 * cfg["count"] * cfg["P"]
+    w = Workload(torch, D, I, dev, cfg, 2 if 2 * resident <= budget_bytes else 1)
+    out = {"workload": cfg["name"], "P": w.P, "dims": w.dims, "count": w.count,
+           "phases": D.ddl_plan_num_steps(w.plan)}
+    sched_bytes = D.ddl_plan_bytes_moved(w.plan)
+    D.ddl_plan_set_replay(w.plan, D.DDL_REPLAY_OFF)
+    out["schedule"] = w.measure(D.ddl_allreduce_sim, K, W, nbytes=sched_bytes)
+    out["learners_identical"] = bool(w.identical(W + K - 1))
+    if sched_bytes / max(out["phases"], 1) < (64 << 20):
+        D.ddl_plan_set_replay(w.plan, D.DDL_REPLAY_ON)
+        out["schedule_graph_replay"] = w.measure(D.ddl_allreduce_sim, K, W, nbytes=sched_bytes)
+        # back to back, no refills and no events between the calls: the launch-bound rate
+        n = 200
+        call = w.entry(D.ddl_allreduce_sim)
+        for mode, key in ((D.DDL_REPLAY_OFF, "eager"), (D.DDL_REPLAY_ON, "graph_replay")):
+            D.ddl_plan_set_replay(w.plan, mode)
+            for b in w.sets[0]:
+                b.zero_()
+            call(0)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(n):
+                call(0)
+            torch.cuda.synchronize()
+            out.setdefault("back_to_back_us", {})[key] = round((time.perf_counter() - t0) / n * 1e6, 2)
+    D.ddl_plan_set_replay(w.plan, D.DDL_REPLAY_AUTO)
+    try:
+        out["fused_variant"] = w.measure(D.ddl_allreduce_fused_sim, K, W, nbytes=D.ddl_plan_fused_bytes(w.plan))
+    except D.DdlError as e:
+        out["fused_variant"] = {"error": str(e)}
+    if "layers" in cfg["name"]:
+        tplan, ntens = w.tensor_plan()
+        if tplan is not None:
+            out["per_tensor_variant"] = w.measure(D.ddl_allreduce_sim, K, W, plan=tplan,
+                                                  nbytes=D.ddl_plan_bytes_moved(tplan))
+            out["per_tensor_variant"]["tensors"] = ntens
+    w.close()
+    return out
+
+
+def box_sweep(torch, D, dev, P=256, iters=30, counts=(4096, 65536, 1 << 20), boxes=None):
     """Sec. 4.3: a ring's time has a latency term per phase, so for many learners a box with
     fewer phases wins although it moves the same bytes.  On one GPU the latency of a phase
-    is a kernel-launch boundary.  Times every box on three buffer sizes, fits
+    is a kernel-launch boundary.  Times every box on several buffer sizes, fits
     T = phases * L + bytes / B by least squares and asks ddl_choose_dims with the fit."""
     import numpy as np
 
-    boxes = [[256], [16, 16], [4, 64], [64, 4], [4, 8, 8], [4, 4, 4, 4], [2] * 8]
+    boxes = boxes or [[256], [16, 16], [4, 64], [64, 4], [4, 8, 8], [4, 4, 4, 4], [2] * 8]
     stream = torch.cuda.current_stream()
     rows = []
-    for count in (4096, 65536, 1 << 20):
+    for count in counts:
         bufs = [torch.zeros(count, dtype=torch.float32, device=dev) for _ in range(P)]
+        ptrs = D.pointer_array(bufs)
         for dims in boxes:
             plan = D.ddl_ring_plan(dims, P, count)
             D.ddl_plan_prepare(plan)
+            D.ddl_plan_set_replay(plan, D.DDL_REPLAY_OFF)
             for _ in range(3):
-                D.ddl_allreduce_sim(bufs, P, plan, count, D.DDL_F32, stream)
+                D.ddl_allreduce_sim(ptrs, P, plan, count, D.DDL_F32, stream)
             torch.cuda.synchronize()
             t0 = time.perf_counter()
             for _ in range(iters):
-                D.ddl_allreduce_sim(bufs, P, plan, count, D.DDL_F32, stream)
+                D.ddl_allreduce_sim(ptrs, P, plan, count, D.DDL_F32, stream)
             torch.cuda.synchronize()
             us = (time.perf_counter() - t0) / iters * 1e6
             rows.append({"count": count, "dims": dims, "phases": D.ddl_plan_num_steps(plan),
                          "bytes": D.ddl_plan_bytes_moved(plan), "us": round(us, 1)})
-        del bufs
+        del bufs, ptrs
     A = np.array([[r["phases"], r["bytes"]] for r in rows], dtype=np.float64)
     y = np.array([r["us"] * 1e-6 for r in rows])
     (L, invB), *_ = np.linalg.lstsq(A, y, rcond=None)
     picks = {}
-    for count in (4096, 65536, 1 << 20):
+    for count in counts:
         dims, t = D.ddl_choose_dims(P, 4 * count, [1.0 / invB / 2.5] * 8, [float(L)] * 8)
         best = min((r for r in rows if r["count"] == count), key=lambda r: r["us"])
+        mine = [r for r in rows if r["count"] == count and [d for d in r["dims"] if d > 1] == [d for d in dims if d > 1]]
         picks[str(count)] = {"chooser": [d for d in dims if d > 1], "modelled_us": round(t * 1e6, 1),
+                             "chooser_measured_us": mine[0]["us"] if mine else None,
                              "fastest_measured": best["dims"], "fastest_us": best["us"]}
-    print(json.dumps({"mode": "box_sweep", "P": P, "iters": iters, "results": rows,
-                      "fit": {"latency_per_phase_us": round(L * 1e6, 3), "bandwidth_GBs": round(1e-9 / invB, 1),
-                              "note": "the chooser's per-link bandwidth is the fitted rate / 2.5: the model "
-                                      "counts 4 bytes per element and transfer, the kernels move 12 or 8"},
-                      "chooser": picks}))
+    return {"P": P, "iters": iters, "results": rows,
+            "fit": {"latency_per_phase_us": round(L * 1e6, 3), "bandwidth_GBs": round(1e-9 / invB, 1),
+                    "note": "the chooser's per-link bandwidth is the fitted rate / 2.5: the model "
+                            "counts 4 bytes per element and transfer, the kernels move 12 or 8"},
+            "chooser": picks}
+
+
+def cpu_baseline(I, cfg, budget_s=30.0):
+    """The oracle's step simulator as it stands, on the host, on a bounded sample."""
+    from concurrent.futures import ThreadPoolExecutor
+
+    from oracle import allreduce_steps  # the CPU baseline leg: the only use of the oracle here
+
+    P, dims, count, dist, seed = cfg["P"], cfg["dims"], cfg["count"], cfg["dist"], cfg["seed"]
+    c_count = count if 4 * count * P <= 8 * 2 ** 30 else count // 16
+    workers = max(1, min(16, os.cpu_count() or 1))
+    with ThreadPoolExecutor(workers) as pool:   # input generation only; the oracle runs on one core
+        V = list(pool.map(lambda j: I.fill_host(c_count, seed, j, dist), range(P)))
+    times = []
+    t_start = time.perf_counter()
+    while len(times) < 5 and time.perf_counter() - t_start < budget_s:
+        t0 = time.perf_counter()
+        allreduce_steps(V, dims)
+        times.append(time.perf_counter() - t0)
+    c_s = sorted(times)[len(times) // 2]
+    cpu = {"value": 4 * c_count / c_s / 1e9, "unit": "GB/s per virtual learner", "cores": 1, "kind": "oracle",
+           "sample": f"numpy step simulator, P={P} dims={dims}, {c_count} of {count} elements per learner "
+                     f"(throughput does not depend on the length once out of cache), median of {len(times)} "
+                     f"passes, {c_s:.2f} s per pass",
+           "hbm_equivalent_GBs": 20 * c_count * (P - 1) / c_s / 1e9,
+           "host_cores_available": os.cpu_count()}
+    # second figure: the same oracle on slabs of the element range, one slab per host core
+    # (the path is element-wise independent; numpy releases the GIL)
+    cuts = [c_count * k // workers // 4 * 4 for k in range(workers)] + [c_count]
+    slabs = [[v[a:b] for v in V] for a, b in zip(cuts, cuts[1:])]
+    with ThreadPoolExecutor(workers) as pool:
+        t0 = time.perf_counter()
+        list(pool.map(lambda sl: allreduce_steps(sl, dims), slabs))
+        a_s = time.perf_counter() - t0
+    cpu["all_cores"] = {"value": 4 * c_count / a_s / 1e9, "unit": "GB/s per virtual learner", "cores": workers,
+                        "kind": "oracle on element slabs, one thread per slab", "seconds": round(a_s, 3)}
+    return cpu
 
 
 def main():
@@ -68,14 +284,18 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", type=int, default=2, help="1-based index into the five configurations")
-    ap.add_argument("--sets-gib", type=float, default=96.0,
-                    help="HBM budget for distinct input sets (one per step until it is used up)")
+    ap.add_argument("--config", type=int, default=5, help="1-based index into the five configurations")
+    ap.add_argument("--dims", type=str, default=None, help="ad-hoc box, e.g. 4,8,8 (instead of --config)")
+    ap.add_argument("--P", type=int, default=None, help="learners of the ad-hoc box (must equal the product of --dims)")
+    ap.add_argument("--count", type=int, default=1 << 20, help="elements per learner of the ad-hoc shape")
+    ap.add_argument("--seed", type=int, default=None, help="generator seed (default: the configuration's)")
+    ap.add_argument("--dist", choices=["int8", "uniform", "normal"], default=None)
+    ap.add_argument("--sets-gib", type=float, default=200.0, help="HBM budget for the input sets (two if they fit)")
+    ap.add_argument("--stagger-kib", type=int, default=0,
+                    help="start learner j's buffer (j mod 4) * this many KiB into its allocation")
     ap.add_argument("--profile-passes", type=int, default=10)
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
-    ap.add_argument("--no-fused", action="store_true", help="skip timing the step-fused variant")
-    ap.add_argument("--per-tensor", action="store_true",
-                    help="also time the per-tensor mode (always done for the per-layer configuration)")
+    ap.add_argument("--no-others", action="store_true", help="skip the secondary configurations and the box sweep")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="also run one plain device-to-device copy of this many MiB (a dispatch of "
                          "known size, to scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
@@ -107,156 +327,75 @@ def main():
                    "peak_used_GBs": HBM_PEAK_GBS, "hbm_bytes": props.total_memory,
                    "compute_units": props.multi_processor_count}
     if args.box_sweep:
-        box_sweep(torch, D, dev)
+        print(json.dumps(dict(mode="box_sweep", **box_sweep(torch, D, dev))))
         return
-    cfg = I.CONFIGS[args.config - 1]
-    P, dims, count, dist, seed = cfg["P"], cfg["dims"], cfg["count"], cfg["dist"], cfg["seed"]
+
+    if args.dims:
+        dims = [int(x) for x in args.dims.split(",")]
+        P = args.P if args.P is not None else prod(dims)
+        dist = args.dist or "uniform"
+        cfg = dict(name=f"adhoc_box{'x'.join(map(str, dims))}_count{args.count}_{dist}", P=P, dims=dims,
+                   count=args.count, dist=dist, seed=args.seed if args.seed is not None else I.BASE_SEED)
+    else:
+        cfg = dict(I.CONFIGS[args.config - 1])
+        if args.seed is not None:
+            cfg["seed"] = args.seed
+        if args.dist is not None:
+            cfg["dist"] = args.dist
+    Workload.stagger_bytes = args.stagger_kib * 1024
     K, W = args.steps, args.warmup
-    plan = D.ddl_ring_plan(dims, P, count)
-    D.ddl_plan_prepare(plan)
-    nsteps = D.ddl_plan_num_steps(plan)
-    bytes_total = D.ddl_plan_bytes_moved(plan)
-    resident = 4 * count * P
+    budget = int(args.sets_gib * 2 ** 30)
+    resident = 4 * cfg["count"] * cfg["P"]
+    w = Workload(torch, D, I, dev, cfg, 2 if 2 * resident <= budget else 1)
+    P, dims, count = w.P, w.dims, w.count
+    nsteps = D.ddl_plan_num_steps(w.plan)
+    bytes_total = D.ddl_plan_bytes_moved(w.plan)
 
-    # Distinct, freshly seeded input sets, so repeated in-place sums neither overflow nor
-    # find the previous step's data in the caches.  If the budget is smaller than K+W sets
-    # the sets are reused round-robin (values grow by a factor P per reuse, timing is
-    # value-independent).
-    n_sets = max(1, min(K + W, int(args.sets_gib * 2 ** 30 // resident)))
-    stream = torch.cuda.current_stream()
-    sets = []
-    for s in range(n_sets):
-        bufs = [torch.empty(count, dtype=torch.float32, device=dev) for _ in range(P)]
-        for j, b in enumerate(bufs):
-            I.fill_device(b, seed + 1000 * s, j, dist, 0, stream)
-        sets.append(bufs)
-    torch.cuda.synchronize()
+    # the schedule itself: `value`
+    head = w.measure(D.ddl_allreduce_sim, K, W, nbytes=bytes_total)
+    same = w.identical(W + K - 1)
+    ms_per_step = head["ms_per_step"]
+    per_learner_gbs = head["GBs_per_virtual_learner"]
 
-    def run(i):
-        D.ddl_allreduce_sim(sets[i % n_sets], P, plan, count, D.DDL_F32, stream)
-
-    for i in range(W):
-        run(i)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(W, W + K):
-        run(i)
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    ms_per_step = elapsed * 1e3 / K
-    per_learner_gbs = 4 * count / (ms_per_step * 1e-3) / 1e9
-    hbm_gbs = bytes_total / (ms_per_step * 1e-3) / 1e9
-
-    # The step-fused variant of the same allreduce (one pass, 8*count*P bytes), rated
-    # against its own byte count; reported beside the schedule's figures, never as `value`.
-    fused = None
-    if not args.no_fused:
-        try:
-            for i in range(W):
-                D.ddl_allreduce_fused_sim(sets[i % n_sets], P, plan, count, D.DDL_F32, stream)
-            torch.cuda.synchronize()
-            t0 = time.perf_counter()
-            for i in range(W, W + K):
-                D.ddl_allreduce_fused_sim(sets[i % n_sets], P, plan, count, D.DDL_F32, stream)
-            torch.cuda.synchronize()
-            f_ms = (time.perf_counter() - t0) * 1e3 / K
-            f_bytes = D.ddl_plan_fused_bytes(plan)
-            fused = {"entry": "ddl_allreduce_fused_sim", "ms_per_step": f_ms,
-                     "GBs_per_virtual_learner": 4 * count / (f_ms * 1e-3) / 1e9,
-                     "bytes": f_bytes, "achieved_GBs": f_bytes / (f_ms * 1e-3) / 1e9,
-                     "frac": f_bytes / (f_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                     "speedup_vs_schedule": ms_per_step / f_ms}
-        except D.DdlError as e:
-            fused = {"entry": "ddl_allreduce_fused_sim", "error": str(e)}
+    # The step-fused variant of the same allreduce, rated against its own byte count;
+    # reported beside the schedule's figures, never as `value`.
+    try:
+        fused = dict(entry="ddl_allreduce_fused_sim",
+                     **w.measure(D.ddl_allreduce_fused_sim, K, W, nbytes=D.ddl_plan_fused_bytes(w.plan)))
+        fused["speedup_vs_schedule"] = ms_per_step / fused["ms_per_step"]
+    except D.DdlError as e:
+        fused = {"entry": "ddl_allreduce_fused_sim", "error": str(e)}
 
     # Per-tensor mode (each layer's tensor reduced on its own, all transfers of a phase in
-    # one launch): timed for the configuration that is defined as a per-layer tensor list,
-    # or on request; rated against its own schedule's bytes.
+    # one launch) where the buffer has a network's size; rated against its own schedule's bytes.
     per_tensor = None
-    if args.per_tensor or "layers" in cfg["name"]:
-        shapes = I.resnet50_shapes() if count == I.RESNET50_COUNT else (
-            I.resnet101_22k_shapes() if count == I.RESNET101_22K_COUNT else None)
-        if shapes is not None:
-            offs, cnts = I.tensor_segments(shapes)
-            tplan = D.ddl_ring_plan_tensors(dims, P, offs, cnts, count)
-            D.ddl_plan_prepare(tplan)
-            for i in range(W):
-                D.ddl_allreduce_sim(sets[i % n_sets], P, tplan, count, D.DDL_F32, stream)
-            torch.cuda.synchronize()
-            t0 = time.perf_counter()
-            for i in range(W, W + K):
-                D.ddl_allreduce_sim(sets[i % n_sets], P, tplan, count, D.DDL_F32, stream)
-            torch.cuda.synchronize()
-            t_ms = (time.perf_counter() - t0) * 1e3 / K
-            t_bytes = D.ddl_plan_bytes_moved(tplan)
-            per_tensor = {"entry": "ddl_ring_plan_tensors + ddl_allreduce_sim", "tensors": len(offs),
-                          "ms_per_step": t_ms, "GBs_per_virtual_learner": 4 * count / (t_ms * 1e-3) / 1e9,
-                          "bytes": t_bytes, "achieved_GBs": t_bytes / (t_ms * 1e-3) / 1e9,
-                          "frac": t_bytes / (t_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                          "slowdown_vs_one_buffer": t_ms / ms_per_step}
-            del tplan
+    tplan, ntens = w.tensor_plan()
+    if tplan is not None:
+        per_tensor = dict(entry="ddl_ring_plan_tensors + ddl_allreduce_sim", tensors=ntens,
+                          **w.measure(D.ddl_allreduce_sim, K, W, plan=tplan, nbytes=D.ddl_plan_bytes_moved(tplan)))
+        per_tensor["slowdown_vs_one_buffer"] = per_tensor["ms_per_step"] / ms_per_step
+        del tplan
 
-    # quick self-check on the last set used: every learner holds the same bits
-    last = sets[(W + K - 1) % n_sets]
-    same = all(torch.equal(last[0].view(torch.int32), last[j].view(torch.int32)) for j in range(1, P))
-
-    # Roofline of the dominant kernel (the reduce-add phase kernel carries 12 of every 20
-    # bytes): HIP events on the stream the kernels run on, one pair round each half of the
-    # allreduce, so that the average launch duration includes kernel-to-kernel gaps but no
-    # event overhead between launches.
-    kinds = [D.ddl_plan_get_step(plan, s)[0] for s in range(nsteps)]
-    step_bytes = [D.ddl_plan_step_bytes(plan, s) for s in range(nsteps)]
-    acc_ms = {D.DDL_STEP_REDUCE: 0.0, D.DDL_STEP_GATHER: 0.0}
-    acc_bytes = {D.DDL_STEP_REDUCE: 0, D.DDL_STEP_GATHER: 0}
-    launches = {D.DDL_STEP_REDUCE: 0, D.DDL_STEP_GATHER: 0}
-    for p in range(args.profile_passes):
-        for j, b in enumerate(sets[p % n_sets]):
-            I.fill_device(b, seed + 7777 + p, j, dist, 0, stream)
-        r_ms, g_ms = D.ddl_allreduce_sim_timed(sets[p % n_sets], P, plan, count, D.DDL_F32, stream)
-        acc_ms[D.DDL_STEP_REDUCE] += r_ms
-        acc_ms[D.DDL_STEP_GATHER] += g_ms
-        for s in range(nsteps):
-            if step_bytes[s]:
-                acc_bytes[kinds[s]] += step_bytes[s]
-                launches[kinds[s]] += 1
-    # per-phase times (diagnostic only: an event pair round every launch adds a few us each)
-    per_step_ms = [0.0] * nsteps
-    if args.profile_passes:
-        for j, b in enumerate(sets[0]):
-            I.fill_device(b, seed + 9999, j, dist, 0, stream)
-        per_step_ms = D.ddl_allreduce_sim_profile(sets[0], P, plan, count, D.DDL_F32, stream)
-
-    def kernel_line(kind, name):
-        if not launches[kind]:
-            return None
-        gbs = acc_bytes[kind] / (acc_ms[kind] * 1e-3) / 1e9
-        return {"kernel": name, "launches": launches[kind],
-                "avg_launch_us": 1e3 * acc_ms[kind] / launches[kind],
-                "avg_launch_bytes": acc_bytes[kind] / launches[kind],
-                "achieved_GBs": gbs, "frac": gbs / HBM_PEAK_GBS}
-
-    red = kernel_line(D.DDL_STEP_REDUCE, "reduce_add_step (step_kernel<float,true>)")
-    cpy = kernel_line(D.DDL_STEP_GATHER, "copy_step (step_kernel<float,false>)")
-    traffic = None
-    tfile = os.path.join(ROOT, "profiles", "traffic.json")
-    if os.path.exists(tfile):
-        try:
-            traffic = json.load(open(tfile)).get(cfg["name"])
-        except (OSError, ValueError):
-            traffic = None
+    red, cpy = kernel_roofline(w, args.profile_passes) if args.profile_passes else (None, None)
+    per_step_ms = []
+    if args.profile_passes:   # diagnostic only: an event pair round every launch adds a few us each
+        w.refill(9999)
+        per_step_ms = D.ddl_allreduce_sim_profile(w.ptrs[9999 % len(w.sets)], P, w.plan, count, D.DDL_F32, w.stream)
+    recorded = RECORDED_TRAFFIC.get(cfg["name"])
     roofline = {"bound": "hbm", "kernel": red["kernel"] if red else None,
                 "achieved": red["achieved_GBs"] if red else None, "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": red["frac"] if red else None, "traffic": traffic,
+                "unit": "GB/s", "frac": red["frac"] if red else None,
+                "traffic": recorded["bytes_per_launch"] if recorded else None,
+                "traffic_source": recorded["source"] if recorded else
+                "none recorded for this workload (counter runs need rocprofv3 around the process)",
                 "bytes_per_element": {"reduce_add_step": 12, "copy_step": 8},
                 "avg_launch_us": red["avg_launch_us"] if red else None,
                 "avg_launch_bytes": red["avg_launch_bytes"] if red else None,
                 "copy_step": cpy,
-                "whole_allreduce": {"achieved": hbm_gbs, "frac": hbm_gbs / HBM_PEAK_GBS,
-                                    "bytes": bytes_total},
+                "whole_allreduce": {"achieved": head["achieved_GBs"], "frac": head["frac"], "bytes": bytes_total},
                 "per_step_us": [round(1e3 * x, 2) for x in per_step_ms]}
-
-    del sets
-    torch.cuda.empty_cache()
+    n_sets = len(w.sets)
+    w.close()
 
     if args.calib_copy_mib > 0:
         a = torch.zeros(args.calib_copy_mib * 2 ** 18, dtype=torch.float32, device=dev)
@@ -266,38 +405,17 @@ def main():
         torch.cuda.synchronize()
         del a, b
 
-    cpu = None
-    if not args.no_cpu:
-        from oracle import allreduce_steps  # the CPU baseline leg: the oracle as it stands
+    others, fit = None, None
+    if not args.no_others:
+        others = [secondary(torch, D, I, dev, c, K, W, budget) for c in I.CONFIGS if c["name"] != cfg["name"]]
+        sweep = box_sweep(torch, D, dev, P=256, iters=20, counts=(4096, 262144),
+                          boxes=[[256], [16, 16], [4, 8, 8], [2] * 8])
+        fit = {"latency_per_phase_us": sweep["fit"]["latency_per_phase_us"],
+               "bandwidth_GBs": sweep["fit"]["bandwidth_GBs"], "chooser": sweep["chooser"],
+               "what": "T = phases * L + schedule bytes / B fitted over 4 boxes of 256 learners x 2 sizes, "
+                       "phases launched kernel by kernel (Sec. 4.3's latency term = a launch boundary)"}
 
-        c_count = count if resident <= 8 * 2 ** 30 else count // 16
-        V = [I.fill_host(c_count, seed, j, dist) for j in range(P)]
-        times = []
-        t_start = time.perf_counter()
-        while len(times) < 5 and time.perf_counter() - t_start < 30.0:   # bounded: at most ~30 s
-            t0 = time.perf_counter()
-            allreduce_steps(V, dims)
-            times.append(time.perf_counter() - t0)
-        c_s = sorted(times)[len(times) // 2]
-        cpu = {"value": 4 * c_count / c_s / 1e9, "unit": "GB/s per virtual learner", "cores": 1,
-               "kind": "oracle",
-               "sample": f"numpy step simulator, P={P} dims={dims}, {c_count} of {count} elements per "
-                         f"learner, median of {len(times)} passes, {c_s:.2f} s per pass",
-               "hbm_equivalent_GBs": 20 * c_count * (P - 1) / c_s / 1e9,
-               "host_cores_available": os.cpu_count()}
-        # optional second figure: the same oracle on slabs of the element range, one slab per
-        # host core (the path is element-wise independent; numpy releases the GIL)
-        from concurrent.futures import ThreadPoolExecutor
-        workers = max(1, min(16, os.cpu_count() or 1))
-        cuts = [c_count * w // workers // 4 * 4 for w in range(workers)] + [c_count]
-        slabs = [[v[a:b] for v in V] for a, b in zip(cuts, cuts[1:])]
-        with ThreadPoolExecutor(workers) as pool:
-            t0 = time.perf_counter()
-            list(pool.map(lambda sl: allreduce_steps(sl, dims), slabs))
-            a_s = time.perf_counter() - t0
-        cpu["all_cores"] = {"value": 4 * c_count / a_s / 1e9, "unit": "GB/s per virtual learner",
-                            "cores": workers, "kind": "oracle on element slabs, one thread per slab",
-                            "seconds": round(a_s, 3)}
+    cpu = None if args.no_cpu else cpu_baseline(I, cfg)
 
     out = {
         "metric": "allreduce GB/s per virtual learner + achieved HBM GB/s (% of peak)",
@@ -306,15 +424,21 @@ def main():
         "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": cfg["name"], "P": P, "dims": dims, "count": count, "dist": dist,
-                   "seed": seed, "phases": nsteps, "resident_bytes": resident,
-                   "input_sets": n_sets, "bus_GBs_per_learner": per_learner_gbs * 2 * (P - 1) / P},
-        "hbm_GBs": hbm_gbs, "hbm_frac_of_peak": hbm_gbs / HBM_PEAK_GBS,
+        "config": {"workload": cfg["name"], "P": P, "dims": dims, "count": count, "dist": cfg["dist"],
+                   "seed": cfg["seed"], "phases": nsteps, "resident_bytes": resident,
+                   "input_sets": n_sets, "refilled_before_every_step": True,
+                   "bus_GBs_per_learner": per_learner_gbs * 2 * (P - 1) / P},
+        "timing": {"method": "one HIP-event pair per step on the launch stream; ms_per_step = median of the steps",
+                   "ms_mean": head["ms_mean"], "ms_min": head["ms_min"], "ms_max": head["ms_max"],
+                   "wall_s_with_refills": head["wall_s_with_refills"]},
+        "hbm_GBs": head["achieved_GBs"], "hbm_frac_of_peak": head["frac"],
         "learners_identical": bool(same),
         "device": device_info,
         "roofline": roofline,
         "fused_variant": fused,
         "per_tensor_variant": per_tensor,
+        "other_configs": others,
+        "latency_fit": fit,
         "cpu_baseline": cpu,
     }
     print(json.dumps(out))

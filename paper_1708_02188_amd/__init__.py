@@ -21,7 +21,7 @@ _BINDING_NAMES = (
     "ddl_plan_fused_bytes",
     "ddl_plan_num_steps", "ddl_plan_num_learners", "ddl_plan_bytes_moved", "ddl_plan_step_bytes",
     "ddl_plan_get_step", "ddl_plan_owned_chunk", "ddl_plan_model_time", "ddl_choose_dims", "ddl_device_memory_info", "ddl_status_string",
-    "library_path",
+    "library_path", "pointer_array",
 )
 __all__ = list(_BINDING_NAMES)
 

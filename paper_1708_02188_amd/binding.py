@@ -106,10 +106,16 @@ def _h(plan):
     return plan.handle if isinstance(plan, Plan) else plan
 
 
+def pointer_array(bufs):
+    """The host array of device pointers the ddl_*_sim calls take, made once from ints or
+    objects with data_ptr(); pass it instead of the list to marshal nothing per call."""
+    return _ptr_array(bufs)
+
+
 def _ptr_array(bufs):
     """Host array of device pointers from ints or objects with data_ptr()."""
-    if bufs is None:
-        return None
+    if bufs is None or isinstance(bufs, ctypes.Array):
+        return bufs
     vals = [b.data_ptr() if hasattr(b, "data_ptr") else b for b in bufs]
     return (ctypes.c_void_p * len(vals))(*vals)
 

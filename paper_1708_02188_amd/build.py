@@ -25,9 +25,15 @@ COMMON = [
     "-ffp-contract=off",
 ]
 
+SIM_SOURCES = ["plan.cpp", "api.cpp", "kernels.hip"]
 LIBS = {
-    "libddlsim.so": ["plan.cpp", "api.cpp", "kernels.hip"],
-    "libddlgen.so": ["ddlgen.hip"],
+    "libddlsim.so": (SIM_SOURCES, []),
+    "libddlgen.so": (["ddlgen.hip"], []),
+    # The same library with tiny launch limits, so that inputs of test size run the paths
+    # that only huge inputs reach otherwise: the kernels' stride over the tiles a capped grid
+    # leaves, and the split of a several-tensor phase into more than one launch.  Loaded by
+    # the GPU tests through DDLSIM_LIBRARY; never by the product.
+    "libddlsim_smallgrid.so": (SIM_SOURCES, ["-DDDL_MAX_GRID_THREADS=65536", "-DDDL_LIST_PER_LAUNCH=1000"]),
 }
 
 
@@ -43,9 +49,9 @@ def build_all(out_dir=None, extra_flags=None, verbose=True):
     extra = list(extra_flags or []) + shlex.split(os.environ.get("DDLSIM_CXXFLAGS", ""))
     os.makedirs(out_dir, exist_ok=True)
     built = []
-    for lib, sources in LIBS.items():
+    for lib, (sources, flags) in LIBS.items():
         out = os.path.join(out_dir, lib)
-        cmd = [hipcc()] + COMMON + extra + ["-o", out] + [os.path.join(CSRC, s) for s in sources]
+        cmd = [hipcc()] + COMMON + flags + extra + ["-o", out] + [os.path.join(CSRC, s) for s in sources]
         if verbose:
             print(" ".join(cmd), flush=True)
         subprocess.run(cmd, check=True)

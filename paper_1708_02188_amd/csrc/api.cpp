@@ -10,6 +10,11 @@
 #include "kernels.h"
 #include "plan.h"
 
+// Learners from which the step-fused allreduce runs as two passes (see run_fused).
+#ifndef DDL_FUSED_TWO_PASS_FROM
+#define DDL_FUSED_TWO_PASS_FROM 16
+#endif
+
 namespace {
 
 using ddl::DeviceTables;
@@ -29,6 +34,7 @@ void release(T** d) {
 void release_binding(ddl::Binding* b) {
     if (b->replay) (void)hipGraphExecDestroy(static_cast<hipGraphExec_t>(b->replay));
     release(&b->rops);
+    release(&b->items);
     release(&b->d_ptrs);
     release(&b->fused_ptrs);
     delete b;
@@ -39,7 +45,8 @@ void release_tables(DeviceTables* t) {
     t->bindings.clear();
     if (t->capture_stream) (void)hipStreamDestroy(static_cast<hipStream_t>(t->capture_stream));
     release(&t->ops);
-    release(&t->descs);
+    release(&t->whole);
+    release(&t->ragged);
     release(&t->fused_seq);
     release(&t->fused_ctl);
     release(&t->fused_n);
@@ -71,7 +78,8 @@ ddl_status_t device_tables_locked(const ddl_plan* plan, DeviceTables** out) {
     t->device = device;
     bool ok = true;
     if (!plan->ops.empty()) ok = upload(&t->ops, plan->ops);
-    if (ok && !plan->descs.empty()) ok = upload(&t->descs, plan->descs);
+    if (ok && !plan->whole.empty()) ok = upload(&t->whole, plan->whole);
+    if (ok && !plan->ragged.empty()) ok = upload(&t->ragged, plan->ragged);
     if (!ok) {
         release_tables(t);
         delete t;
@@ -115,6 +123,7 @@ ddl::Binding* new_binding(const ddl_plan* plan, const DeviceTables* t, bool fuse
     ddl::Binding* b = new (std::nothrow) ddl::Binding;
     if (b == nullptr) return nullptr;
     bool ok = plan->ops.empty() || reserve(&b->rops, plan->ops.size());
+    if (ok && !plan->whole.empty()) ok = reserve(&b->items, plan->whole.size());
     if (ok && plan->P > ddl::kKernargLearners) ok = reserve(&b->d_ptrs, size_t(plan->P));
     if (ok && fused) ok = reserve(&b->fused_ptrs, size_t(plan->P) * size_t(t->fused_padded));
     if (!ok) {
@@ -185,8 +194,10 @@ ddl_status_t acquire_binding(void** bufs, int P, const ddl_plan* plan, hipStream
             if (ddl::launch_store_pointers(bufs, P, slot->d_ptrs, stream) != hipSuccess) return DDL_ERR_HIP;
             d_ptrs = slot->d_ptrs;
         }
-        const hipError_t err = fused ? ddl::launch_fused_resolve(*plan, *t, slot->fused_ptrs, table, d_ptrs, stream)
-                                     : ddl::launch_resolve(*plan, t->ops, slot->rops, table, d_ptrs, stream);
+        hipError_t err = fused ? ddl::launch_fused_resolve(*plan, *t, slot->fused_ptrs, table, d_ptrs, stream)
+                               : ddl::launch_resolve(*plan, t->ops, slot->rops, table, d_ptrs, stream);
+        if (err == hipSuccess && !fused)
+            err = ddl::launch_resolve_items(*plan, slot->rops, t->whole, slot->items, stream);
         if (err != hipSuccess) return DDL_ERR_HIP;
         if (capturing) slot->pinned = true;
         else if (fused) slot->fused_valid = true;
@@ -228,10 +239,8 @@ ddl_status_t check_call(void** bufs, int P, const ddl_plan* plan, size_t count, 
 // Enqueue the kernels of steps [first, last) for the slot's buffers.
 ddl_status_t launch_steps(const ddl_plan* plan, const DeviceTables* t, const ddl::Binding* slot, int first,
                           int last, hipStream_t stream, hipEvent_t* events) {
-    const size_t per_step = size_t(plan->P) * plan->seg_off.size();
     for (int s = first; s < last; ++s) {
-        if (ddl::launch_step(*plan, plan->steps[s], slot->rops + size_t(s) * per_step, t->descs, stream) !=
-            hipSuccess)
+        if (ddl::launch_step(*plan, plan->steps[s], slot->rops, slot->items, t->ragged, stream) != hipSuccess)
             return DDL_ERR_HIP;
         if (events && hipEventRecord(events[s - first + 1], stream) != hipSuccess) return DDL_ERR_HIP;
     }
@@ -448,7 +457,7 @@ ddl_status_t ddl_allreduce_sim_noalloc(void** bufs, int P, const ddl_plan_t* pla
     std::memcpy(table.p, bufs, size_t(P) * sizeof(void*));
     if (ddl::launch_resolve_from_box(*plan, table, records, stream) != hipSuccess) return DDL_ERR_HIP;
     for (size_t s = 0; s < steps; ++s)
-        if (ddl::launch_step(*plan, plan->steps[s], records + s * size_t(P), nullptr, stream) != hipSuccess)
+        if (ddl::launch_step(*plan, plan->steps[s], records, nullptr, nullptr, stream) != hipSuccess)
             return DDL_ERR_HIP;
     return DDL_OK;
 }
@@ -493,7 +502,7 @@ ddl_status_t run_fused(void** bufs, int P, const ddl_plan* plan, size_t count, d
     bool ok;
     if (which == 1) ok = pass(1);
     else if (which == 2) ok = pass(2);
-    else if (P >= 32) ok = pass(1) && pass(2);
+    else if (P >= DDL_FUSED_TWO_PASS_FROM) ok = pass(1) && pass(2);
     else ok = pass(0);
     return ok ? DDL_OK : DDL_ERR_HIP;
 }
@@ -597,7 +606,7 @@ size_t ddl_plan_bytes_moved(const ddl_plan_t* plan) { return plan ? plan->bytes_
 size_t ddl_plan_fused_bytes(const ddl_plan_t* plan) {
     if (plan == nullptr) return 0;
     // one pass: P reads + P writes per element; two passes: one more write and read
-    const size_t per_elem = plan->P >= 32 ? size_t(2) * plan->P + 2 : size_t(2) * plan->P;
+    const size_t per_elem = plan->P >= DDL_FUSED_TWO_PASS_FROM ? size_t(2) * plan->P + 2 : size_t(2) * plan->P;
     return per_elem * plan->elem_size * plan->count;
 }
 

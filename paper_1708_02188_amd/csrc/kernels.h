@@ -96,11 +96,17 @@ hipError_t launch_resolve_from_box(const ddl_plan& plan, const PtrTable& table, 
 hipError_t launch_resolve(const ddl_plan& plan, const Op* d_ops, ResolvedOp* d_rops,
                           const PtrTable& table, void* const* d_ptrs, hipStream_t stream);
 
-// Enqueue the kernel of one step.  d_rops points at that step's resolved operations in
-// device memory; d_descs at the plan's work list (several-tensor plans, else unused).
+// Enqueue the kernel of one step (`step` must be an element of plan.steps).  d_rops points at
+// the plan's whole table of resolved operations in device memory; d_items / d_ragged at the
+// bound whole items and the ragged work list (several-tensor plans, else unused).
 // A step that moves nothing enqueues nothing.
-hipError_t launch_step(const ddl_plan& plan, const Step& step, const ResolvedOp* d_rops,
-                       const BlockDesc* d_descs, hipStream_t stream);
+hipError_t launch_step(const ddl_plan& plan, const Step& step, const ResolvedOp* d_rops, const ItemRec* d_items,
+                       const BlockDesc* d_ragged, hipStream_t stream);
+
+// Several-tensor plans: bind the whole work items (d_whole, plan.whole.size() of them) to
+// the buffers d_rops was resolved for.  Enqueue after launch_resolve on the same stream.
+hipError_t launch_resolve_items(const ddl_plan& plan, const ResolvedOp* d_rops, const BlockDesc* d_whole,
+                                ItemRec* d_items, hipStream_t stream);
 
 // Plain copy of n elements with the all-gather phase's streaming shape.
 hipError_t launch_assign(ddl_dtype_t dtype, void* dst, const void* src, uint64_t n, hipStream_t stream);

@@ -49,6 +49,11 @@
 #ifndef DDL_NT_STORE
 #define DDL_NT_STORE 1
 #endif
+// A launch stays below this many threads; the kernels stride over what is left.  (A build
+// with a small value makes small inputs take the striding paths: that is how they are tested.)
+#ifndef DDL_MAX_GRID_THREADS
+#define DDL_MAX_GRID_THREADS (uint64_t(1) << 32)
+#endif
 
 namespace ddl {
 namespace {
@@ -262,7 +267,8 @@ hipError_t launch_assign_typed(void* dst, const void* src, uint64_t n, hipStream
     constexpr uint64_t VL = 16 / sizeof(typename Elem<T>::S);
     constexpr uint64_t TILE = uint64_t(DDL_THREADS) * DDL_UNROLL;
     uint64_t tiles = (n / VL + 1 + (kRowVecs - 1) + TILE - 1) / TILE;
-    const uint64_t max_x = (uint64_t(1) << 32) / DDL_THREADS - 1;
+    uint64_t max_x = DDL_MAX_GRID_THREADS / DDL_THREADS - 1;
+    if (max_x == 0) max_x = 1;
     if (tiles > max_x) tiles = max_x;
     hipLaunchKernelGGL((assign_kernel<T>), dim3(static_cast<unsigned>(tiles)), dim3(DDL_THREADS), 0, stream,
                        reinterpret_cast<uint64_t>(src), reinterpret_cast<uint64_t>(dst), n,
@@ -271,33 +277,55 @@ hipError_t launch_assign_typed(void* dst, const void* src, uint64_t n, hipStream
 }
 
 // Several-tensor plans: the phase's transfers differ in length by orders of magnitude, so
-// the launch is a flat list of work items (operation, first row).  Items that hold all
-// kListRows rows come first and get one single-wave workgroup per row, like the
-// single-tensor kernel; the short items that hold the rest of each operation (all there
-// is of a tiny tensor's chunk) get one workgroup each, which walks their kListTailRows rows.
+// the launch is a flat list of work items.  Whole items (kListRows interior rows of one
+// operation) come first and get one single-wave workgroup per row, like the single-tensor
+// kernel; their addresses were bound to the call's buffers beforehand (resolve_items), so
+// the workgroup's prologue is one 16-byte scalar load and needs no bounds.  The ragged items
+// that hold the first and last rows of each operation (all there is of a tiny tensor's
+// chunk) get one workgroup each, which walks their rows with bounds checks.
+__global__ __launch_bounds__(256) void resolve_items(const ResolvedOp* __restrict__ rops,
+                                                     const BlockDesc* __restrict__ whole,
+                                                     ItemRec* __restrict__ out, unsigned total) {
+    const unsigned i = blockIdx.x * 256u + threadIdx.x;
+    if (i >= total) return;
+    const BlockDesc item = whole[i];
+    const ResolvedOp rec = rops[item.op];
+    const uint64_t shift = (rec.dst % kRowBytes) / 16;
+    const uint64_t byte_off = (uint64_t(item.row) * 64 - shift) * 16;   // row >= 1: never negative
+    ItemRec r;
+    r.src = rec.src + byte_off;
+    r.dst = rec.dst + byte_off;
+    out[i] = r;
+}
+
+typedef uint64_t u64x2 __attribute__((ext_vector_type(2)));
+
 template <typename T, bool REDUCE>
 __global__ __launch_bounds__(64) void step_kernel_list(const ResolvedOp* __restrict__ rops,
-                                                       const BlockDesc* __restrict__ descs,
-                                                       unsigned whole_blocks, unsigned whole_items,
-                                                       unsigned block_offset) {
+                                                       const ItemRec* __restrict__ items,
+                                                       const BlockDesc* __restrict__ ragged,
+                                                       unsigned whole_blocks, unsigned block_offset) {
     static_assert(DDL_THREADS * DDL_UNROLL == 64, "a row is one wave's worth of vectors");
     typedef typename Elem<T>::V V;
     constexpr int64_t VL = 16 / sizeof(typename Elem<T>::S);
     const unsigned b = blockIdx.x + block_offset;
-    const bool whole = b < whole_blocks;
-    const unsigned t = b - whole_blocks;
-    const BlockDesc item = descs[whole ? b / kListRows : whole_items + t];
+    if (b < whole_blocks) {
+        const u64x2 rec = *reinterpret_cast<const u64x2*>(items + b / kListRows);
+        const uint64_t row_off = uint64_t(b % kListRows) * kRowBytes;
+        const DDL_GLOBAL V* s = (const DDL_GLOBAL V*)(rec.x + row_off) + threadIdx.x;
+        DDL_GLOBAL V* d = (DDL_GLOBAL V*)(rec.y + row_off) + threadIdx.x;
+        V a = stream_load(s);
+        if (REDUCE) a = Elem<T>::sum(stream_load((const DDL_GLOBAL V*)d), a);
+        stream_store(d, a);
+        return;
+    }
+    const BlockDesc item = ragged[b - whole_blocks];
     const u64x4 rec = *reinterpret_cast<const u64x4*>(rops + item.op);
     const DDL_GLOBAL V* src = (const DDL_GLOBAL V*)rec.x;
     DDL_GLOBAL V* dst = (DDL_GLOBAL V*)rec.y;
     const int64_t n = int64_t(rec.z);
     const int64_t nv = n / VL;
     const int64_t shift = int64_t((rec.y % kRowBytes) / 16);
-    if (whole) {
-        const int64_t first = (int64_t(item.row) + b % kListRows) * 64 - shift;
-        if (first <= nv) step_tile<T, REDUCE>(src, dst, n, nv, first, threadIdx.x);
-        return;
-    }
     for (int k = 0; k < kListTailRows; ++k) {
         const int64_t first = (int64_t(item.row) + k) * 64 - shift;
         if (first > nv) break;
@@ -305,25 +333,30 @@ __global__ __launch_bounds__(64) void step_kernel_list(const ResolvedOp* __restr
     }
 }
 
+// Workgroups one launch of the list kernel holds at most (64 threads each: below 2^32 threads).
+#ifndef DDL_LIST_PER_LAUNCH
+#define DDL_LIST_PER_LAUNCH ((uint64_t(1) << 26) - 1)
+#endif
+
 template <typename T>
-hipError_t launch_list_typed(const Step& step, const ResolvedOp* d_rops, const BlockDesc* d_descs,
-                             hipStream_t stream) {
-    if (step.desc_count == 0) return hipSuccess;
-    const uint64_t whole_blocks = uint64_t(step.desc_whole) * kListRows;
-    const uint64_t blocks = whole_blocks + uint64_t(step.desc_count - step.desc_whole);
+hipError_t launch_list_typed(const Step& step, const ResolvedOp* d_rops, const ItemRec* d_items,
+                             const BlockDesc* d_ragged, hipStream_t stream) {
+    static_assert(kListHeadRows == kListTailRows, "the head of an operation is one ragged item");
+    const uint64_t whole_blocks = uint64_t(step.whole_count) * kListRows;
+    const uint64_t blocks = whole_blocks + uint64_t(step.ragged_count);
+    if (blocks == 0) return hipSuccess;
     if (blocks > 0xFFFFFFFFull) return hipErrorInvalidValue;
-    // one launch holds at most 2^26 - 1 workgroups (64 threads each, below 2^32 threads)
-    const uint64_t per_launch = (uint64_t(1) << 26) - 1;
+    const uint64_t per_launch = DDL_LIST_PER_LAUNCH;
     for (uint64_t start = 0; start < blocks; start += per_launch) {
         const uint64_t now = blocks - start < per_launch ? blocks - start : per_launch;
         const dim3 grid(static_cast<unsigned>(now), 1, 1);
         if (step.kind == DDL_STEP_REDUCE)
             hipLaunchKernelGGL((step_kernel_list<T, true>), grid, dim3(64), 0, stream, d_rops,
-                               d_descs + step.desc_first, unsigned(whole_blocks), unsigned(step.desc_whole),
+                               d_items + step.whole_first, d_ragged + step.ragged_first, unsigned(whole_blocks),
                                unsigned(start));
         else
             hipLaunchKernelGGL((step_kernel_list<T, false>), grid, dim3(64), 0, stream, d_rops,
-                               d_descs + step.desc_first, unsigned(whole_blocks), unsigned(step.desc_whole),
+                               d_items + step.whole_first, d_ragged + step.ragged_first, unsigned(whole_blocks),
                                unsigned(start));
         const hipError_t err = hipGetLastError();
         if (err != hipSuccess) return err;
@@ -339,8 +372,9 @@ hipError_t launch_typed(const ddl_plan& plan, const Step& step, const ResolvedOp
     // slots to cover: the whole vectors, one for a short last vector, and the row shift
     uint64_t tiles = (step.max_n / VL + 1 + (kRowVecs - 1) + TILE - 1) / TILE;
     // keep gridDim.x * gridDim.y * blockDim.x below 2^32; the kernel strides over the rest
-    const uint64_t max_x = ((uint64_t(1) << 32) / DDL_THREADS - 1) / uint64_t(plan.P);
+    const uint64_t max_x = (DDL_MAX_GRID_THREADS / DDL_THREADS - 1) / uint64_t(plan.P);
     if (tiles > max_x) tiles = max_x;
+    if (tiles == 0) tiles = 1;
     const dim3 grid(static_cast<unsigned>(tiles), static_cast<unsigned>(plan.P), 1);
     const dim3 block(DDL_THREADS, 1, 1);
     if (step.kind == DDL_STEP_REDUCE)
@@ -390,6 +424,17 @@ __device__ __forceinline__ void fused_feed(X (&acc)[DDL_FUSED_MAX_LEVELS], X v, 
     }
 }
 
+// Stores of one value to many learners (single-pass form, distribution pass).
+#ifndef DDL_GATHER_NT
+#define DDL_GATHER_NT 0
+#endif
+template <typename V> __device__ __forceinline__ void gather_store(DDL_GLOBAL V* p, V v) {
+#if DDL_GATHER_NT
+    __builtin_nontemporal_store(v, p);
+#else
+    *p = v;
+#endif
+}
 // What one pass of the fused kernel stores at every place of a finest chunk.
 enum { FUSED_ALL = 0,      // the result to all learners (single-pass form)
        FUSED_REDUCE = 1 }; // the result to the chunk's owner only (first pass of two)
@@ -421,7 +466,7 @@ __device__ __forceinline__ void fused_place(const DDL_CONST uint64_t* row, const
     for (int i0 = 0; i0 < P; i0 += kFusedBatch) {
 #pragma unroll
         for (int j = 0; j < kFusedBatch; ++j)
-            if (i0 + j < P) stream_store((DDL_GLOBAL X*)(row[i0 + j] + byte_off), result);
+            if (i0 + j < P) gather_store((DDL_GLOBAL X*)(row[i0 + j] + byte_off), result);
     }
 }
 
@@ -451,37 +496,60 @@ __global__ __launch_bounds__(64) void fused_kernel(const uint64_t* ptrs_, const 
     }
 }
 
-// Distribution pass of the two-pass form: workgroup (tile, destination group, chunk) reads
-// one row of the chunk from its owner and stores it to the learners of its group.
-// Measured: the fewer groups the better (a group per destination re-reads the row P-1
-// times and, although those reads hit in cache, they still cross the fabric); the default
-// puts all destinations into one group.
-#ifndef DDL_GATHER_GROUP
-#define DDL_GATHER_GROUP DDL_FUSED_MAX_LEARNERS
+// Distribution pass of the two-pass form: every wave reads DDL_GATHER_ROWS consecutive rows of
+// a chunk from its owner, keeps them in registers and stores them to all other learners.
+// Measured on MI355X (one chunk to 15 / 63 / 255 destinations): the shape of the workgroup
+// hardly matters; plain stores beat non-temporal ones by 3-10 % here, and four waves of
+// four rows are the best of the shapes tried.  Splitting the destinations over several
+// workgroups that re-read the rows from cache is never better.
+#ifndef DDL_GATHER_ROWS
+#define DDL_GATHER_ROWS 4
+#endif
+#ifndef DDL_GATHER_WAVES
+#define DDL_GATHER_WAVES 4
 #endif
 template <typename T>
-__global__ __launch_bounds__(64) void fused_gather_kernel(const uint64_t* ptrs_, const uint64_t* chunk_n_,
-                                                          int P, int padded, unsigned tile_stride) {
+__global__ __launch_bounds__(64 * DDL_GATHER_WAVES) void fused_gather_kernel(const uint64_t* ptrs_,
+                                                                             const uint64_t* chunk_n_, int P,
+                                                                             int padded, unsigned tile_stride) {
     typedef typename Elem<T>::V V;
     typedef typename Elem<T>::S S;
     constexpr int64_t VL = 16 / sizeof(S);
-    const DDL_CONST uint64_t* row = (const DDL_CONST uint64_t*)ptrs_ + size_t(blockIdx.z) * padded;
-    const int64_t n = int64_t(((const DDL_CONST uint64_t*)chunk_n_)[blockIdx.z]);
+    constexpr int R = DDL_GATHER_ROWS;
+    constexpr int64_t kWaveVecs = int64_t(R) * 64;                      // vectors per wave
+    constexpr int64_t kTileVecs = kWaveVecs * DDL_GATHER_WAVES;         // vectors per workgroup
+    const DDL_CONST uint64_t* row = (const DDL_CONST uint64_t*)ptrs_ + size_t(blockIdx.y) * padded;
+    const int64_t n = int64_t(((const DDL_CONST uint64_t*)chunk_n_)[blockIdx.y]);
     const int64_t nv = n / VL;
     const uint64_t src_addr = row[P - 1];
     const int64_t shift = int64_t((src_addr % kRowBytes) / 16);
-    const int j0 = blockIdx.y * DDL_GATHER_GROUP;
-    const int j1 = j0 + DDL_GATHER_GROUP < P - 1 ? j0 + DDL_GATHER_GROUP : P - 1;
-    const int64_t tid = threadIdx.x;
-    for (int64_t first = int64_t(blockIdx.x) * 64 - shift; first <= nv; first += int64_t(tile_stride) * 64) {
-        const int64_t v = first + tid;
-        if (v >= 0 && v < nv) {
-            const V x = stream_load((const DDL_GLOBAL V*)src_addr + v);
-            for (int j = j0; j < j1; ++j) stream_store((DDL_GLOBAL V*)row[j] + v, x);
-        } else if (v == nv) {
-            for (int64_t e = nv * VL; e < n; ++e) {
-                const S x = ((const DDL_GLOBAL S*)src_addr)[e];
-                for (int j = j0; j < j1; ++j) ((DDL_GLOBAL S*)row[j])[e] = x;
+    const int64_t lane = threadIdx.x % 64;
+    const int64_t wave = threadIdx.x / 64;
+    for (int64_t tile = int64_t(blockIdx.x) * kTileVecs - shift; tile <= nv; tile += int64_t(tile_stride) * kTileVecs) {
+        const int64_t first = tile + wave * kWaveVecs;   // this wave's R rows: vectors [first, first + R * 64)
+        if (first >= 0 && first + kWaveVecs <= nv) {
+            V x[R];
+#pragma unroll
+            for (int r = 0; r < R; ++r) x[r] = stream_load((const DDL_GLOBAL V*)src_addr + first + r * 64 + lane);
+            for (int j = 0; j < P - 1; ++j) {
+                DDL_GLOBAL V* d = (DDL_GLOBAL V*)row[j] + first + lane;
+#pragma unroll
+                for (int r = 0; r < R; ++r) gather_store(d + r * 64, x[r]);
+            }
+        } else {
+            // first or last rows of the chunk: per-lane bounds
+            for (int r = 0; r < R; ++r) {
+                const int64_t v = first + r * 64 + lane;
+                if (v >= 0 && v < nv) {
+                    const V x = ((const DDL_GLOBAL V*)src_addr)[v];
+                    for (int j = 0; j < P - 1; ++j) ((DDL_GLOBAL V*)row[j])[v] = x;
+                } else if (v == nv) {
+                    // the buffer's last, short vector: element by element
+                    for (int64_t e = nv * VL; e < n; ++e) {
+                        const S x = ((const DDL_GLOBAL S*)src_addr)[e];
+                        for (int j = 0; j < P - 1; ++j) ((DDL_GLOBAL S*)row[j])[e] = x;
+                    }
+                }
             }
         }
     }
@@ -492,8 +560,9 @@ hipError_t launch_fused_typed(const ddl_plan& plan, const DeviceTables& t, const
                               int padded, int levels, uint64_t max_chunk, int mode, hipStream_t stream) {
     constexpr uint64_t VL = 16 / sizeof(typename Elem<T>::S);
     uint64_t tiles = (max_chunk / VL + 1 + (kRowVecs - 1) + 63) / 64;
-    const uint64_t max_x = ((uint64_t(1) << 32) / 64 - 1) / uint64_t(plan.P);
+    const uint64_t max_x = (DDL_MAX_GRID_THREADS / 64 - 1) / uint64_t(plan.P);
     if (tiles > max_x) tiles = max_x;
+    if (tiles == 0) tiles = 1;
     const dim3 grid(static_cast<unsigned>(tiles), static_cast<unsigned>(plan.P), 1);
     if (mode == FUSED_ALL)
         hipLaunchKernelGGL((fused_kernel<T, FUSED_ALL>), grid, dim3(64), 0, stream, fused_ptrs,
@@ -502,12 +571,14 @@ hipError_t launch_fused_typed(const ddl_plan& plan, const DeviceTables& t, const
         hipLaunchKernelGGL((fused_kernel<T, FUSED_REDUCE>), grid, dim3(64), 0, stream, fused_ptrs,
                            t.fused_ctl, t.fused_n, plan.P, padded, levels, grid.x);
     else {
-        const unsigned groups = static_cast<unsigned>((plan.P - 1 + DDL_GATHER_GROUP - 1) / DDL_GATHER_GROUP);
-        const uint64_t max_x3 = ((uint64_t(1) << 32) / 64 - 1) / (uint64_t(plan.P) * groups);
-        const unsigned x = static_cast<unsigned>(tiles > max_x3 ? max_x3 : tiles);
-        const dim3 grid3(x ? x : 1, groups, static_cast<unsigned>(plan.P));
-        hipLaunchKernelGGL((fused_gather_kernel<T>), grid3, dim3(64), 0, stream, fused_ptrs, t.fused_n,
-                           plan.P, padded, grid3.x);
+        constexpr uint64_t kTileVecs = uint64_t(DDL_GATHER_ROWS) * 64 * DDL_GATHER_WAVES;
+        constexpr uint64_t kThreads = 64 * DDL_GATHER_WAVES;
+        uint64_t wide = (max_chunk / VL + 1 + (kRowVecs - 1) + kTileVecs - 1) / kTileVecs;
+        const uint64_t max_w = (DDL_MAX_GRID_THREADS / kThreads - 1) / uint64_t(plan.P);
+        if (wide > max_w) wide = max_w;
+        const dim3 grid2(static_cast<unsigned>(wide ? wide : 1), static_cast<unsigned>(plan.P), 1);
+        hipLaunchKernelGGL((fused_gather_kernel<T>), grid2, dim3(kThreads), 0, stream, fused_ptrs, t.fused_n,
+                           plan.P, padded, grid2.x);
     }
     return hipGetLastError();
 }
@@ -575,19 +646,30 @@ hipError_t launch_resolve_from_box(const ddl_plan& plan, const PtrTable& table, 
     return hipGetLastError();
 }
 
-hipError_t launch_step(const ddl_plan& plan, const Step& step, const ResolvedOp* d_rops,
-                       const BlockDesc* d_descs, hipStream_t stream) {
+hipError_t launch_resolve_items(const ddl_plan& plan, const ResolvedOp* d_rops, const BlockDesc* d_whole,
+                                ItemRec* d_items, hipStream_t stream) {
+    const unsigned total = static_cast<unsigned>(plan.whole.size());
+    if (total == 0) return hipSuccess;
+    hipLaunchKernelGGL(resolve_items, dim3((total + 255) / 256), dim3(256), 0, stream, d_rops, d_whole, d_items,
+                       total);
+    return hipGetLastError();
+}
+
+hipError_t launch_step(const ddl_plan& plan, const Step& step, const ResolvedOp* d_rops, const ItemRec* d_items,
+                       const BlockDesc* d_ragged, hipStream_t stream) {
     if (step.max_n == 0) return hipSuccess;
     if (plan.seg_off.size() > 1) {
+        // the lists index the plan's whole table: d_rops is the first step's
         switch (plan.dtype) {
-            case DDL_F32: return launch_list_typed<float>(step, d_rops, d_descs, stream);
-            case DDL_F64: return launch_list_typed<double>(step, d_rops, d_descs, stream);
-            case DDL_I32: return launch_list_typed<unsigned>(step, d_rops, d_descs, stream);
-            case DDL_F16: return launch_list_typed<_Float16>(step, d_rops, d_descs, stream);
-            case DDL_BF16: return launch_list_typed<bf16_bits>(step, d_rops, d_descs, stream);
+            case DDL_F32: return launch_list_typed<float>(step, d_rops, d_items, d_ragged, stream);
+            case DDL_F64: return launch_list_typed<double>(step, d_rops, d_items, d_ragged, stream);
+            case DDL_I32: return launch_list_typed<unsigned>(step, d_rops, d_items, d_ragged, stream);
+            case DDL_F16: return launch_list_typed<_Float16>(step, d_rops, d_items, d_ragged, stream);
+            case DDL_BF16: return launch_list_typed<bf16_bits>(step, d_rops, d_items, d_ragged, stream);
         }
         return hipErrorInvalidValue;
     }
+    d_rops += size_t(&step - plan.steps.data()) * size_t(plan.P);
     switch (plan.dtype) {
         case DDL_F32: return launch_typed<float>(plan, step, d_rops, stream);
         case DDL_F64: return launch_typed<double>(plan, step, d_rops, stream);

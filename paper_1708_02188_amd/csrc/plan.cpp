@@ -77,8 +77,7 @@ void build_schedule(ddl_plan* plan) {
 
     auto emit = [&](int kind, int t, int phase) {
         const int d = plan->dims[t];
-        Step st{kind, t, 0, 0, plan->descs.size(), 0, 0};
-        std::vector<BlockDesc> ragged;
+        Step st{kind, t, 0, 0, plan->whole.size(), 0, plan->ragged.size(), 0};
         const uint64_t per_elem = (kind == DDL_STEP_REDUCE ? 3u : 2u) * plan->elem_size;
         for (int s = 0; s < S; ++s) {
             for (int r = 0; r < P; ++r) {
@@ -97,25 +96,26 @@ void build_schedule(ddl_plan* plan) {
                 if (op.n > st.max_n) st.max_n = op.n;
                 st.bytes += op.n * per_elem;
                 if (S > 1 && op.n > 0) {
-                    // work list for the batched launch: spans of kListRows 1 KiB rows; one
-                    // row more than the vectors need, because the tiling is shifted onto
-                    // absolute row boundaries at run time.  Whole spans go to the front of
-                    // the phase's slice; what is left of each operation is cut into short
-                    // spans of kListTailRows rows that go to its back.
-                    const uint64_t rows = (op.n / G + 1 + 63 + 63) / 64;
-                    const uint32_t index = static_cast<uint32_t>(plan->ops.size() % (size_t(S) * P));
-                    uint64_t row = 0;
-                    for (; row + kListRows <= rows; row += kListRows)
-                        plan->descs.push_back(BlockDesc{index, static_cast<uint32_t>(row)});
-                    for (; row < rows; row += kListTailRows)
-                        ragged.push_back(BlockDesc{index, static_cast<uint32_t>(row)});
+                    // work lists for the batched launch (see BlockDesc)
+                    const uint64_t nv = op.n / G;                      // whole vectors
+                    const uint64_t rows = (nv + 1 + 63 + 63) / 64;     // one more: the shifted tiling
+                    const uint32_t index = static_cast<uint32_t>(plan->ops.size());
+                    const uint64_t inside = nv / 64;                   // rows [1, inside) are interior
+                    uint64_t whole_end = kListHeadRows;
+                    if (inside > uint64_t(kListHeadRows))
+                        whole_end += (inside - kListHeadRows) / kListRows * kListRows;
+                    for (uint64_t row = 0; row < rows && row < uint64_t(kListHeadRows); row += kListTailRows)
+                        plan->ragged.push_back(BlockDesc{index, static_cast<uint32_t>(row)});
+                    for (uint64_t row = kListHeadRows; row < whole_end; row += kListRows)
+                        plan->whole.push_back(BlockDesc{index, static_cast<uint32_t>(row)});
+                    for (uint64_t row = whole_end; row < rows; row += kListTailRows)
+                        plan->ragged.push_back(BlockDesc{index, static_cast<uint32_t>(row)});
                 }
                 plan->ops.push_back(op);
             }
         }
-        st.desc_whole = plan->descs.size() - st.desc_first;
-        plan->descs.insert(plan->descs.end(), ragged.begin(), ragged.end());
-        st.desc_count = plan->descs.size() - st.desc_first;
+        st.whole_count = plan->whole.size() - st.whole_first;
+        st.ragged_count = plan->ragged.size() - st.ragged_first;
         plan->bytes_total += st.bytes;
         plan->steps.push_back(st);
     };

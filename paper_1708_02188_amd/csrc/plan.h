@@ -30,24 +30,36 @@ struct ResolvedOp {
 };
 static_assert(sizeof(ResolvedOp) == 32, "one 32-byte scalar load per workgroup");
 
-// Work item of a phase of a several-tensor plan: rows [row, row + kListRows) of operation
-// `op` (index within the phase), a row being 64 lanes x 16 bytes; the rows an operation has
-// beyond a multiple of kListRows form items of kListTailRows rows.
+// Work items of a phase of a several-tensor plan.  A row is 64 lanes x 16 bytes of the
+// kernels' tiling, which is laid on absolute 1 KiB boundaries of the destination at run time
+// (row r of an operation of nv whole vectors covers its vectors [64 r - shift, 64 r + 64 -
+// shift), 0 <= shift < 64).  Rows kListHeadRows .. and on, as long as kListRows of them end
+// at or before vector nv, lie inside the operation whatever the shift: they form "whole"
+// items of kListRows rows, whose addresses are bound per call (ItemRec) so that a workgroup
+// finds its row with one 16-byte load.  The rows before and after them form "ragged" items
+// of up to kListTailRows rows that one workgroup walks with bounds checks.
+// `op` indexes the plan's whole operation table (phase-major).
 constexpr int kListRows = 16;
 constexpr int kListTailRows = 4;
+constexpr int kListHeadRows = 4;
 struct BlockDesc {
     uint32_t op;
     uint32_t row;
 };
+// A whole item bound to one call's buffers: addresses of its first row in source and destination.
+struct ItemRec {
+    uint64_t src;
+    uint64_t dst;
+};
+static_assert(sizeof(ItemRec) == 16, "one 16-byte scalar load per workgroup");
 
 struct Step {
     int kind;           // DDL_STEP_REDUCE / DDL_STEP_GATHER
     int dim;            // 0-based box dimension whose rings run in this phase
     uint64_t max_n;     // longest operation of the phase (sizes the launch)
     uint64_t bytes;     // memory traffic of the phase
-    size_t desc_first;  // several-tensor plans: this phase's slice of the work list,
-    size_t desc_count;  // of which the first desc_whole items have all kListRows rows
-    size_t desc_whole;
+    size_t whole_first, whole_count;    // several-tensor plans: this phase's slices of the
+    size_t ragged_first, ragged_count;  // whole and ragged work lists
 };
 
 // Tables of the step-fused allreduce.  Finest chunk c (owned by learner c) is summed over
@@ -67,6 +79,7 @@ constexpr uint32_t kFusedValid = 0x80000000u;
 struct Binding {
     std::vector<void*> key;           // the P learner pointers (empty: never bound)
     ResolvedOp* rops = nullptr;       // the plan's operations for these buffers, step-major
+    ItemRec* items = nullptr;         // several-tensor plans: the whole work items for these buffers
     void** d_ptrs = nullptr;          // the pointers on the device, when P exceeds the kernarg table
     uint64_t* fused_ptrs = nullptr;   // step-fused path: P * padded absolute addresses (on demand)
     bool rops_valid = false;          // an eager call has enqueued the kernel that fills rops for `key`
@@ -80,7 +93,8 @@ struct Binding {
 struct DeviceTables {
     int device = -1;
     Op* ops = nullptr;           // num_steps * P operations, step-major
-    BlockDesc* descs = nullptr;  // work list of a several-tensor plan
+    BlockDesc* whole = nullptr;   // work lists of a several-tensor plan
+    BlockDesc* ragged = nullptr;
     // step-fused path, created at its first use
     uint32_t* fused_seq = nullptr;    // P * padded learner ranks
     uint32_t* fused_ctl = nullptr;    // padded control words
@@ -105,7 +119,7 @@ struct ddl_plan {
     std::vector<ddl::Step> steps;
     std::vector<uint64_t> seg_off, seg_count;  // the tensors inside every learner's buffer (S >= 1)
     std::vector<ddl::Op> ops;             // steps.size() * S * P, step-major, then tensor, then sender
-    std::vector<ddl::BlockDesc> descs;    // work list, only when S > 1
+    std::vector<ddl::BlockDesc> whole, ragged;  // work lists, only when S > 1
     std::vector<uint64_t> own_off, own_n; // finest chunk per (tensor, learner)
     uint64_t bytes_total = 0;
 

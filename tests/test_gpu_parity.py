@@ -538,6 +538,69 @@ def test_more_learners_than_the_kernarg_table_holds(dev):
         assert_bitwise(got[j], want, f"learner={j}")
 
 
+STRIDE_PATHS_CHILD = r"""
+import sys
+from math import prod
+import numpy as np, torch
+import oracle.ddl_oracle as O
+import paper_1708_02188_amd as D
+assert D.library_path().endswith("libddlsim_smallgrid.so"), D.library_path()
+dev = torch.device("cuda:0")
+rng = np.random.default_rng(2024)
+def up(V): return [torch.from_numpy(np.ascontiguousarray(v.view(np.int16) if v.dtype == np.uint16 else v)).to(dev) for v in V]
+def check(bufs, want, what):
+    torch.cuda.synchronize()
+    for j, b in enumerate(bufs):
+        g = b.cpu().numpy().view(want[j].dtype) if isinstance(want, list) else b.cpu().numpy().view(want.dtype)
+        w = want[j] if isinstance(want, list) else want
+        assert g.tobytes() == w.tobytes(), f"{what}: learner {j} differs"
+    print("ok", what, flush=True)
+# a launch holds 65536 threads: (1023 // P) tiles of 1 KiB per operation, the kernels stride over the rest
+for dims, count in (([4, 4], 1_000_003), ([2], 300_001), ([4, 8, 8], 300_001)):
+    P = prod(dims)
+    V = [(rng.uniform(-1, 1, count) * 10.0 ** rng.uniform(-3, 3, count)).astype(np.float32) for _ in range(P)]
+    plan = D.ddl_ring_plan(dims, P, count)
+    want = O.allreduce_fold(V, dims)
+    b = up(V); D.ddl_allreduce_sim(b, P, plan, count); check(b, want, f"phases {dims} {count}")
+    b = up(V); D.ddl_allreduce_fused_sim(b, P, plan, count); check(b, want, f"fused {dims} {count}")
+    b = up(V); D.ddl_allreduce_sim_noalloc(b, P, plan, count); check(b, want, f"noalloc {dims} {count}")
+# 16-bit elements
+dims, count, P = [3, 2], 700_001, 6
+V = [O.f32_to_bf16(rng.uniform(-1, 1, count).astype(np.float32)) for _ in range(P)]
+plan = D.ddl_ring_plan(dims, P, count, D.DDL_BF16)
+b = up(V); D.ddl_allreduce_sim(b, P, plan, count, D.DDL_BF16); check(b, O.allreduce_steps(V, dims, add=O.bf16_add), "bf16 phases")
+b = up(V); D.ddl_allreduce_fused_sim(b, P, plan, count, D.DDL_BF16); check(b, O.allreduce_fold(V, dims, add=O.bf16_add), "bf16 fused")
+# assignment of one long range
+src = torch.arange(2_000_003, device=dev, dtype=torch.float32); dst = torch.zeros_like(src)
+D.ddl_assign_sim(dst, src, src.numel()); torch.cuda.synchronize(); assert torch.equal(src, dst); print("ok assign", flush=True)
+# several-tensor plan: a phase of more than 1000 workgroups is split into several launches
+dims, P = [4, 2], 8
+segments, count = [(0, 64), (64, 100_000), (100_064, 7), (100_072, 1_500_001), (1_600_076, 33)], 1_600_076 + 33
+V = [(rng.uniform(-1, 1, count) * 10.0 ** rng.uniform(-3, 3, count)).astype(np.float32) for _ in range(P)]
+plan = D.ddl_ring_plan_tensors(dims, P, [o for o, _ in segments], [n for _, n in segments], count)
+b = up(V); D.ddl_allreduce_sim(b, P, plan, count); check(b, O.allreduce_tensors(V, dims, segments), "tensor plan, split launches")
+print("stride paths ok")
+"""
+
+
+def test_striding_and_split_launch_paths_in_a_small_grid_build(dev):
+    """Every kernel strides over the tiles its grid does not cover once an operation exceeds
+    2^32 / 64 workgroups, and a several-tensor phase of more than 2^26 workgroups is split
+    into several launches.  libddlsim_smallgrid.so is the same source built with those
+    limits set to 65536 threads and 1000 workgroups, so inputs of test size run exactly
+    those paths; a fresh process loads it and is checked against the oracle."""
+    import os
+    import subprocess
+    from conftest import ROOT
+    lib = os.path.join(os.path.dirname(D.library_path()), "libddlsim_smallgrid.so")
+    assert os.path.exists(lib), "build it with python -m paper_1708_02188_amd.build"
+    env = dict(os.environ, DDLSIM_LIBRARY=lib)
+    run = subprocess.run([sys.executable, "-c", STRIDE_PATHS_CHILD], cwd=ROOT, capture_output=True, text=True,
+                         timeout=600, env=env)
+    say(run.stdout)
+    assert run.returncode == 0 and "stride paths ok" in run.stdout, run.stderr[-3000:]
+
+
 # ---------------------------------------------------------------------------------------
 # seeded random sweep over boxes, lengths, element types and entry points
 # ---------------------------------------------------------------------------------------
@@ -640,37 +703,6 @@ def test_tensor_plan_sixteen_bit(dev):
         assert_bitwise(g, want[j], f"bf16 tensor plan learner={j}")
 
 
-def test_config3_per_tensor_mode_full_size(dev):
-    """Configuration 3 as 161 independent per-layer allreduces (P=64, dims [4,16])."""
-    cfg = I.CONFIGS[2]
-    P, dims, count, dist, seed = cfg["P"], cfg["dims"], cfg["count"], cfg["dist"], cfg["seed"]
-    offs, cnts = I.tensor_segments(I.resnet50_shapes())
-    say(f"config 3 per-tensor: {len(offs)} tensors, smallest {min(cnts)}, largest {max(cnts)}")
-    bufs = [torch.empty(count, dtype=torch.float32, device=dev) for _ in range(P)]
-    for j, b in enumerate(bufs):
-        I.fill_device(b, seed, j, dist)
-    plan = D.ddl_ring_plan_tensors(dims, P, offs, cnts, count)
-    D.ddl_allreduce_sim(bufs, P, plan, count, D.DDL_F32, torch.cuda.current_stream())
-    torch.cuda.synchronize()
-    for j in range(1, P):
-        assert torch.equal(bufs[0].view(torch.int32), bufs[j].view(torch.int32)), f"learner {j} differs"
-    got = bufs[0].cpu().numpy()
-    del bufs
-    torch.cuda.empty_cache()
-    # every small tensor whole, the large ones on sampled ranges
-    rng = np.random.default_rng(3)
-    checked = 0
-    for off, n in zip(offs, cnts):
-        ranges = [(0, n)] if n <= 8192 else [(0, 2048), (n - 2048, n)] + [
-            (int(a), int(a) + 1024) for a in rng.integers(0, n - 1024, 2)]
-        for a, b in ranges:
-            want = O.allreduce_fold_range(
-                lambda r, lo, hi: I.fill_host(hi - lo, seed, r, dist, first=off + lo), dims, n, a, b, np.float32)
-            assert_bitwise(got[off + a:off + b], want, f"tensor at {off} elements [{a},{b})")
-            checked += b - a
-    say(f"  {checked} elements checked against the oracle")
-
-
 # ---------------------------------------------------------------------------------------
 # step-fused allreduce: same final bits as the phase-by-phase schedule
 # ---------------------------------------------------------------------------------------
@@ -757,28 +789,6 @@ def test_fused_allreduce_many_learners_and_limits(dev):
     assert e.value.status == D.DDL_ERR_UNSUPPORTED
 
 
-@pytest.mark.parametrize("idx", [1, 3])
-def test_fused_allreduce_full_size(dev, idx):
-    cfg = I.CONFIGS[idx]
-    P, dims, count, dist, seed = cfg["P"], cfg["dims"], cfg["count"], cfg["dist"], cfg["seed"]
-    say(f"fused config {cfg['name']}")
-    bufs = [torch.empty(count, dtype=torch.float32, device=dev) for _ in range(P)]
-    for j, b in enumerate(bufs):
-        I.fill_device(b, seed, j, dist)
-    plan = D.ddl_ring_plan(dims, P, count)
-    D.ddl_allreduce_fused_sim(bufs, P, plan, count, D.DDL_F32, torch.cuda.current_stream())
-    torch.cuda.synchronize()
-    for j in range(1, P):
-        assert torch.equal(bufs[0].view(torch.int32), bufs[j].view(torch.int32)), f"learner {j} differs"
-    got = bufs[0].cpu().numpy()
-    del bufs
-    torch.cuda.empty_cache()
-    for a, b in sample_ranges(plan, P, count):
-        want = O.allreduce_fold_range(lambda r, lo, hi: I.fill_host(hi - lo, seed, r, dist, first=lo),
-                                      dims, count, a, b, np.float32)
-        assert_bitwise(got[a:b], want, f"fused {cfg['name']} [{a},{b})")
-
-
 # ---------------------------------------------------------------------------------------
 # the benchmark configurations at full size, device-generated inputs
 # ---------------------------------------------------------------------------------------
@@ -798,44 +808,91 @@ def sample_ranges(plan, P, count, width=2048, extra=12):
     return [(a, b) for a, b in ranges if b > a]
 
 
-def run_config(dev, cfg, full_compare):
-    P, dims, count, dist, seed = cfg["P"], cfg["dims"], cfg["count"], cfg["dist"], cfg["seed"]
-    say(f"config {cfg['name']}: P={P} dims={dims} count={count} dist={dist} seed={seed}")
+PIECE = 1 << 17   # elements the oracle folds per task (P * PIECE * 4 bytes of inputs per worker)
+WORKERS = 16      # the GPU machine's CPU share
+
+
+def compare_whole(results, dims, seed, dist, tensors, what):
+    """Every element of `results` (name -> learner 0's buffer on the host) against the oracle's
+    nested fold, computed piece by piece on a thread pool straight from the generator
+    (numpy and the generator release the GIL).  `tensors` = [(offset, length)]: each is
+    chunked and reduced on its own; a one-buffer plan is the single tensor (0, count)."""
+    import time
+    from concurrent.futures import ThreadPoolExecutor
+
+    tasks = [(off, n, a, min(n, a + PIECE)) for off, n in tensors for a in range(0, n, PIECE)]
+
+    def one(task):
+        off, n, a, b = task
+        want = O.allreduce_fold_range(lambda r, lo, hi: I.fill_host(hi - lo, seed, r, dist, first=off + lo),
+                                      dims, n, a, b, np.float32)
+        for name, got in results.items():
+            assert_bitwise(got[off + a:off + b], want, f"{what} {name}: tensor at {off}, elements [{a},{b})")
+        return b - a
+
+    t0 = time.perf_counter()
+    with ThreadPoolExecutor(WORKERS) as pool:
+        compared = sum(pool.map(one, tasks))
+    say(f"  {what}: {compared} elements x {len(results)} result(s) compared with the oracle, every one equal, "
+        f"{len(tasks)} pieces, {time.perf_counter() - t0:.1f} s")
+    return compared
+
+
+def fp64_closeness(got, P, dims, count, seed, dist, ranges):
+    """|x - fp64 sum| <= 1e-5 * sum_j |V_j| per element and <= 1e-5 * max|fp64 sum| overall."""
+    worst = 0.0
+    for a, b in ranges:
+        V = [I.fill_host(b - a, seed, r, dist, first=a) for r in range(P)]
+        ref = O.sum_fp64(V)
+        absum = sum(np.abs(v.astype(np.float64)) for v in V)
+        err = np.abs(got[a:b].astype(np.float64) - ref)
+        assert np.all(err <= 1e-5 * absum)
+        if dist == "int8":
+            assert np.array_equal(got[a:b].astype(np.float64), ref)  # integers: exact
+        worst = max(worst, float(np.max(err)) / max(float(np.max(np.abs(ref))), 1e-30))
+    assert worst <= 1e-5
+    return worst
+
+
+def device_result(dev, cfg, entry, plan):
+    """Run `entry` on the configuration's device-generated inputs; all learners must hold the
+    same bits; returns learner 0's buffer on the host."""
+    P, count, dist, seed = cfg["P"], cfg["count"], cfg["dist"], cfg["seed"]
     bufs = [torch.empty(count, dtype=torch.float32, device=dev) for _ in range(P)]
     for j, b in enumerate(bufs):
         I.fill_device(b, seed, j, dist)
-    plan = D.ddl_ring_plan(dims, P, count)
     torch.cuda.synchronize()
-    say("  inputs resident, launching")
-    D.ddl_allreduce_sim(bufs, P, plan, count, D.DDL_F32, torch.cuda.current_stream())
+    entry(bufs, P, plan, count, D.DDL_F32, torch.cuda.current_stream())
     torch.cuda.synchronize()
-    say("  allreduce done, checking learners agree")
     for j in range(1, P):
         assert torch.equal(bufs[0].view(torch.int32), bufs[j].view(torch.int32)), f"learner {j} differs from 0"
     got = bufs[0].cpu().numpy()
     del bufs
     torch.cuda.empty_cache()
+    return got
 
-    def get(r, a, b):
-        return I.fill_host(b - a, seed, r, dist, first=a)
 
-    ranges = [(0, count)] if full_compare else sample_ranges(plan, P, count)
-    say(f"  oracle on {len(ranges)} ranges, {sum(b - a for a, b in ranges)} elements")
-    worst_rel = 0.0
-    for a, b in ranges:
-        want = O.allreduce_fold_range(get, dims, count, a, b, np.float32)
-        assert_bitwise(got[a:b], want, f"{cfg['name']} elements [{a},{b})")
-        if not full_compare or b - a <= 1 << 22:
-            V = [get(r, a, b) for r in range(P)]
-            ref = O.sum_fp64(V)
-            absum = sum(np.abs(v.astype(np.float64)) for v in V)
-            err = np.abs(got[a:b].astype(np.float64) - ref)
-            assert np.all(err <= 1e-5 * absum)
-            if dist == "int8":
-                assert np.array_equal(got[a:b].astype(np.float64), ref)  # integers: exact
-            worst_rel = max(worst_rel, float(np.max(err)) / max(float(np.max(np.abs(ref))), 1e-30))
-    assert worst_rel <= 1e-5
-    say(f"  ok, worst |x - fp64| / max|fp64| = {worst_rel:.2e}")
+def run_config(dev, cfg, fused=True, per_tensor=False):
+    """One benchmark configuration at full size: the phase-by-phase schedule and the
+    step-fused form, whole buffer of learner 0 against the oracle (the other learners are
+    compared with learner 0 on the device), fp64 closeness on sampled ranges."""
+    P, dims, count, dist, seed = cfg["P"], cfg["dims"], cfg["count"], cfg["dist"], cfg["seed"]
+    say(f"config {cfg['name']}: P={P} dims={dims} count={count} dist={dist} seed={seed}")
+    plan = D.ddl_ring_plan(dims, P, count)
+    results = {"ddl_allreduce_sim": device_result(dev, cfg, D.ddl_allreduce_sim, plan)}
+    if fused:
+        results["ddl_allreduce_fused_sim"] = device_result(dev, cfg, D.ddl_allreduce_fused_sim, plan)
+    assert compare_whole(results, dims, seed, dist, [(0, count)], cfg["name"]) == count
+    worst = fp64_closeness(results["ddl_allreduce_sim"], P, dims, count, seed, dist, sample_ranges(plan, P, count))
+    say(f"  fp64 closeness on sampled ranges: worst |x - fp64| / max|fp64| = {worst:.2e}")
+    if per_tensor:
+        shapes = I.resnet50_shapes() if count == I.RESNET50_COUNT else I.resnet101_22k_shapes()
+        offs, cnts = I.tensor_segments(shapes)
+        tplan = D.ddl_ring_plan_tensors(dims, P, offs, cnts, count)
+        got = device_result(dev, cfg, D.ddl_allreduce_sim, tplan)
+        n = compare_whole({"per-tensor plan": got}, dims, seed, dist, list(zip(offs, cnts)),
+                          f"{cfg['name']} as {len(offs)} tensors")
+        assert n == count
 
 
 def test_buffers_beyond_four_gibibytes(dev):
@@ -860,40 +917,39 @@ def test_buffers_beyond_four_gibibytes(dev):
 
 
 def test_config1_ring4_integer_exact(dev):
-    run_config(dev, I.CONFIGS[0], full_compare=True)
+    run_config(dev, I.CONFIGS[0])
 
 
-def test_config2_box4x4_resnet50_full_compare(dev):
-    cfg = I.CONFIGS[1]
-    run_config(dev, cfg, full_compare=True)
+def test_config2_box4x4_resnet50_whole_buffer(dev):
+    run_config(dev, I.CONFIGS[1], per_tensor=True)
 
 
 def test_config2_first_range_fp64(dev):
     # fp64 closeness over a 4 M element prefix of the ResNet-50-sized buffer
-    cfg = dict(I.CONFIGS[1])
-    P, dims, count = cfg["P"], cfg["dims"], cfg["count"]
-    bufs = [torch.empty(count, dtype=torch.float32, device=dev) for _ in range(P)]
-    for j, b in enumerate(bufs):
-        I.fill_device(b, cfg["seed"], j, cfg["dist"])
-    plan = D.ddl_ring_plan(dims, P, count)
-    D.ddl_allreduce_sim(bufs, P, plan, count)
-    torch.cuda.synchronize()
-    n = 1 << 22
-    got = bufs[3][:n].cpu().numpy().astype(np.float64)
-    V = [I.fill_host(n, cfg["seed"], r, cfg["dist"]) for r in range(P)]
-    ref = O.sum_fp64(V)
-    absum = sum(np.abs(v.astype(np.float64)) for v in V)
-    assert np.all(np.abs(got - ref) <= 1e-5 * absum)
-    assert np.max(np.abs(got - ref)) <= 1e-5 * np.max(np.abs(ref))
+    cfg = I.CONFIGS[1]
+    plan = D.ddl_ring_plan(cfg["dims"], cfg["P"], cfg["count"])
+    got = device_result(dev, cfg, D.ddl_allreduce_sim, plan)
+    fp64_closeness(got, cfg["P"], cfg["dims"], cfg["count"], cfg["seed"], cfg["dist"], [(0, 1 << 22)])
 
 
-def test_config3_box4x16_resnet50_layers(dev):
-    run_config(dev, I.CONFIGS[2], full_compare=False)
+def test_config3_box4x16_resnet50_layers_whole_buffer(dev):
+    run_config(dev, I.CONFIGS[2], per_tensor=True)
 
 
-def test_config4_box4x8x8_resnet50(dev):
-    run_config(dev, I.CONFIGS[3], full_compare=False)
+def test_config4_box4x8x8_resnet50_whole_buffer(dev):
+    run_config(dev, I.CONFIGS[3])
 
 
-def test_config5_box4x8x8_resnet101_22k(dev):
-    run_config(dev, I.CONFIGS[4], full_compare=False)
+def test_config5_box4x8x8_resnet101_22k_whole_buffer(dev):
+    run_config(dev, I.CONFIGS[4])
+
+
+def test_config5_per_tensor_plan_whole_buffer(dev):
+    """Configuration 5's buffer as the 314 tensors of ResNet-101 with the 22K-class head."""
+    cfg = I.CONFIGS[4]
+    offs, cnts = I.tensor_segments(I.resnet101_22k_shapes())
+    tplan = D.ddl_ring_plan_tensors(cfg["dims"], cfg["P"], offs, cnts, cfg["count"])
+    got = device_result(dev, cfg, D.ddl_allreduce_sim, tplan)
+    n = compare_whole({"per-tensor plan": got}, cfg["dims"], cfg["seed"], cfg["dist"], list(zip(offs, cnts)),
+                      f"{cfg['name']} as {len(offs)} tensors")
+    assert n == cfg["count"]

@@ -35,8 +35,30 @@ static void one(const std::vector<int>& dims, uint64_t count, ddl_dtype_t dtype,
     if (plan.ops.size() != steps * off.size() * (size_t)P) std::abort();
     for (const ddl::Op& op : plan.ops)
         if (op.off + op.n > count || op.src < 0 || op.src >= P || op.dst < 0 || op.dst >= P) std::abort();
-    for (const ddl::BlockDesc& d : plan.descs)
-        if (d.op >= off.size() * (size_t)P) std::abort();
+    // work lists: whole items are interior rows of their operation, every row of the shifted
+    // tiling is covered exactly once
+    const uint64_t G = 16 / (uint64_t)plan.elem_size;
+    if (off.size() > 1) {
+        std::vector<uint64_t> covered(plan.ops.size(), 0);
+        for (const ddl::BlockDesc& d : plan.whole) {
+            if (d.op >= plan.ops.size()) std::abort();
+            const uint64_t nv = plan.ops[d.op].n / G;
+            if (d.row < 1 || (uint64_t(d.row) + ddl::kListRows) * 64 > nv) std::abort();
+            covered[d.op] += ddl::kListRows;
+        }
+        for (const ddl::BlockDesc& d : plan.ragged) {
+            if (d.op >= plan.ops.size()) std::abort();
+            const uint64_t rows = (plan.ops[d.op].n / G + 1 + 63 + 63) / 64;
+            if (d.row >= rows) std::abort();
+            covered[d.op] += rows - d.row < (uint64_t)ddl::kListTailRows ? rows - d.row : ddl::kListTailRows;
+        }
+        for (size_t i = 0; i < plan.ops.size(); ++i) {
+            const uint64_t rows = plan.ops[i].n ? (plan.ops[i].n / G + 1 + 63 + 63) / 64 : 0;
+            if (covered[i] != rows) std::abort();
+        }
+    } else if (!plan.whole.empty() || !plan.ragged.empty()) {
+        std::abort();
+    }
     int levels = 0;
     for (int d : dims) levels += d > 1;
     if (P <= 64 && levels >= 1) {
@@ -58,6 +80,7 @@ int main() {
                 if (c > 100000 && dims.size() > 3) continue;
                 one(dims, c, t, {0}, {c});
                 if (c >= 64) one(dims, c, t, {0, 16, 48}, {9, 32, c - 48});
+                if (c >= 600000) one(dims, c, t, {0, 300000}, {299999, c - 300000});
             }
     int dims3[3];
     double bw[3] = {2e10, 1e10, 9.5e9}, lat[3] = {1e-5, 1e-5, 1e-5}, time = 0;
