@@ -228,7 +228,7 @@ ddl_status_t ddl_assign_sim(void* dst, const void* src, size_t count, ddl_dtype_
  * registers and writes the result to every learner, instead of executing the phases one
  * by one.  The partial sums the phases would have left in the buffers on the way are never
  * materialised.  Memory traffic is 2 * sizeof(element) * count * P bytes instead of
- * ddl_plan_bytes_moved; from 32 learners on the work is split into a reducing pass (result
+ * ddl_plan_bytes_moved; from 16 learners on the work is split into a reducing pass (result
  * to the chunk's owner) and a distributing pass, which adds one write and one read of the
  * result (ddl_plan_fused_bytes gives the exact figure).
  * Same arguments, rules and errors as ddl_allreduce_sim; additionally

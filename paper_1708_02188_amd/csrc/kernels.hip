@@ -304,14 +304,30 @@ template <typename T, bool REDUCE>
 __global__ __launch_bounds__(64) void step_kernel_list(const ResolvedOp* __restrict__ rops,
                                                        const ItemRec* __restrict__ items,
                                                        const BlockDesc* __restrict__ ragged,
-                                                       unsigned whole_blocks, unsigned block_offset) {
+                                                       unsigned whole_blocks, unsigned ragged_count,
+                                                       unsigned period, unsigned block_offset) {
     static_assert(DDL_THREADS * DDL_UNROLL == 64, "a row is one wave's worth of vectors");
     typedef typename Elem<T>::V V;
-    constexpr int64_t VL = 16 / sizeof(typename Elem<T>::S);
+    typedef typename Elem<T>::S S;
+    constexpr int64_t VL = 16 / sizeof(S);
+    // Ragged items are latency-bound (a chain of two table loads, then rows with bounds):
+    // they are spread evenly through the launch, the last workgroup of every `period`,
+    // so that the streaming rows around them hide them.
     const unsigned b = blockIdx.x + block_offset;
-    if (b < whole_blocks) {
-        const u64x2 rec = *reinterpret_cast<const u64x2*>(items + b / kListRows);
-        const uint64_t row_off = uint64_t(b % kListRows) * kRowBytes;
+    unsigned q, w;
+    bool whole;
+    if (period == 0) {   // all ragged items after the whole rows
+        whole = b < whole_blocks;
+        w = b;
+        q = b - whole_blocks;
+    } else {
+        q = b / period;
+        whole = b % period != period - 1 || q >= ragged_count;
+        w = b - (q < ragged_count ? q : ragged_count);   // index among the whole rows
+    }
+    if (whole) {
+        const u64x2 rec = *reinterpret_cast<const u64x2*>(items + w / kListRows);
+        const uint64_t row_off = uint64_t(w % kListRows) * kRowBytes;
         const DDL_GLOBAL V* s = (const DDL_GLOBAL V*)(rec.x + row_off) + threadIdx.x;
         DDL_GLOBAL V* d = (DDL_GLOBAL V*)(rec.y + row_off) + threadIdx.x;
         V a = stream_load(s);
@@ -319,17 +335,39 @@ __global__ __launch_bounds__(64) void step_kernel_list(const ResolvedOp* __restr
         stream_store(d, a);
         return;
     }
-    const BlockDesc item = ragged[b - whole_blocks];
+    const BlockDesc item = ragged[q];
     const u64x4 rec = *reinterpret_cast<const u64x4*>(rops + item.op);
     const DDL_GLOBAL V* src = (const DDL_GLOBAL V*)rec.x;
     DDL_GLOBAL V* dst = (DDL_GLOBAL V*)rec.y;
     const int64_t n = int64_t(rec.z);
     const int64_t nv = n / VL;
     const int64_t shift = int64_t((rec.y % kRowBytes) / 16);
+    // all rows of the item at once: loads first, then the stores
+    const int64_t v0 = int64_t(item.row) * 64 - shift + threadIdx.x;
+    V a[kListTailRows], c[kListTailRows];
+#pragma unroll
     for (int k = 0; k < kListTailRows; ++k) {
-        const int64_t first = (int64_t(item.row) + k) * 64 - shift;
-        if (first > nv) break;
-        step_tile<T, REDUCE>(src, dst, n, nv, first, threadIdx.x);
+        const int64_t v = v0 + k * 64;
+        if (v >= 0 && v < nv) {
+            a[k] = src[v];
+            if (REDUCE) c[k] = dst[v];
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < kListTailRows; ++k) {
+        const int64_t v = v0 + k * 64;
+        if (v >= 0 && v < nv) {
+            dst[v] = REDUCE ? Elem<T>::sum(c[k], a[k]) : a[k];
+        } else if (v == nv) {
+            // the buffer's last, short vector: element by element
+            const DDL_GLOBAL S* se = (const DDL_GLOBAL S*)(src + nv);
+            DDL_GLOBAL S* de = (DDL_GLOBAL S*)(dst + nv);
+            for (int64_t e = 0; e < n - nv * VL; ++e) {
+                S x = se[e];
+                if (REDUCE) x = Elem<T>::sum(de[e], x);
+                de[e] = x;
+            }
+        }
     }
 }
 
@@ -339,7 +377,7 @@ __global__ __launch_bounds__(64) void step_kernel_list(const ResolvedOp* __restr
 #endif
 
 template <typename T>
-hipError_t launch_list_typed(const Step& step, const ResolvedOp* d_rops, const ItemRec* d_items,
+hipError_t launch_list_typed(const Step& step, int learners, const ResolvedOp* d_rops, const ItemRec* d_items,
                              const BlockDesc* d_ragged, hipStream_t stream) {
     static_assert(kListHeadRows == kListTailRows, "the head of an operation is one ragged item");
     const uint64_t whole_blocks = uint64_t(step.whole_count) * kListRows;
@@ -347,17 +385,26 @@ hipError_t launch_list_typed(const Step& step, const ResolvedOp* d_rops, const I
     if (blocks == 0) return hipSuccess;
     if (blocks > 0xFFFFFFFFull) return hipErrorInvalidValue;
     const uint64_t per_launch = DDL_LIST_PER_LAUNCH;
+    // Measured on MI355X with ResNet-sized tensor lists: spreading the ragged items through
+    // the launch gains 2-3 % with 16 and 64 learners and loses 15 % with 256, where the
+    // ragged items of one phase touch small ranges of some five hundred different buffers
+    // (and so evict the address translations the streaming rows use); then they go last.
+#ifndef DDL_LIST_INTERLEAVE_MAX_LEARNERS
+#define DDL_LIST_INTERLEAVE_MAX_LEARNERS 64
+#endif
+    const unsigned period = learners <= DDL_LIST_INTERLEAVE_MAX_LEARNERS && step.ragged_count
+                                ? static_cast<unsigned>(blocks / step.ragged_count) : 0u;
     for (uint64_t start = 0; start < blocks; start += per_launch) {
         const uint64_t now = blocks - start < per_launch ? blocks - start : per_launch;
         const dim3 grid(static_cast<unsigned>(now), 1, 1);
         if (step.kind == DDL_STEP_REDUCE)
             hipLaunchKernelGGL((step_kernel_list<T, true>), grid, dim3(64), 0, stream, d_rops,
                                d_items + step.whole_first, d_ragged + step.ragged_first, unsigned(whole_blocks),
-                               unsigned(start));
+                               unsigned(step.ragged_count), period, unsigned(start));
         else
             hipLaunchKernelGGL((step_kernel_list<T, false>), grid, dim3(64), 0, stream, d_rops,
                                d_items + step.whole_first, d_ragged + step.ragged_first, unsigned(whole_blocks),
-                               unsigned(start));
+                               unsigned(step.ragged_count), period, unsigned(start));
         const hipError_t err = hipGetLastError();
         if (err != hipSuccess) return err;
     }
@@ -661,11 +708,11 @@ hipError_t launch_step(const ddl_plan& plan, const Step& step, const ResolvedOp*
     if (plan.seg_off.size() > 1) {
         // the lists index the plan's whole table: d_rops is the first step's
         switch (plan.dtype) {
-            case DDL_F32: return launch_list_typed<float>(step, d_rops, d_items, d_ragged, stream);
-            case DDL_F64: return launch_list_typed<double>(step, d_rops, d_items, d_ragged, stream);
-            case DDL_I32: return launch_list_typed<unsigned>(step, d_rops, d_items, d_ragged, stream);
-            case DDL_F16: return launch_list_typed<_Float16>(step, d_rops, d_items, d_ragged, stream);
-            case DDL_BF16: return launch_list_typed<bf16_bits>(step, d_rops, d_items, d_ragged, stream);
+            case DDL_F32: return launch_list_typed<float>(step, plan.P, d_rops, d_items, d_ragged, stream);
+            case DDL_F64: return launch_list_typed<double>(step, plan.P, d_rops, d_items, d_ragged, stream);
+            case DDL_I32: return launch_list_typed<unsigned>(step, plan.P, d_rops, d_items, d_ragged, stream);
+            case DDL_F16: return launch_list_typed<_Float16>(step, plan.P, d_rops, d_items, d_ragged, stream);
+            case DDL_BF16: return launch_list_typed<bf16_bits>(step, plan.P, d_rops, d_items, d_ragged, stream);
         }
         return hipErrorInvalidValue;
     }

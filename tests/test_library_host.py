@@ -162,7 +162,9 @@ def test_assign_argument_errors():
 def test_fused_limits_and_bytes():
     plan = D.ddl_ring_plan([4, 8, 8], 256, 25557032)
     assert D.ddl_plan_fused_bytes(plan) == 4 * 25557032 * (2 * 256 + 2)
-    assert D.ddl_plan_fused_bytes(D.ddl_ring_plan([4, 4], 16, 1000)) == 4 * 1000 * 32
+    # two passes from 16 learners on (one more write and read of the result), one pass below
+    assert D.ddl_plan_fused_bytes(D.ddl_ring_plan([4, 4], 16, 1000)) == 4 * 1000 * (2 * 16 + 2)
+    assert D.ddl_plan_fused_bytes(D.ddl_ring_plan([4, 2], 8, 1000)) == 4 * 1000 * 16
     assert D.ddl_plan_fused_bytes(None) == 0
     # rejected on the host, before any device work: too many learners / too many levels
     big = D.ddl_ring_plan([2048], 2048, 64)
