@@ -154,24 +154,25 @@ def kernel_roofline(w, passes):
 
 def secondary(torch, D, I, dev, cfg, K, W, budget_bytes):
     """A configuration other than the headline one: the schedule, the step-fused variant and,
-    where the buffer is a layer list, the per-tensor variant; small ones also under graph
-    replay of the phases."""
+    where the buffer is a layer list, the per-tensor variant, and the ring-walk form (one
+    launch per dimension); small ones also back to back."""
     resident = 4 * cfg["count"] * cfg["P"]
     w = Workload(torch, D, I, dev, cfg, 2 if 2 * resident <= budget_bytes else 1)
     out = {"workload": cfg["name"], "P": w.P, "dims": w.dims, "count": w.count,
            "phases": D.ddl_plan_num_steps(w.plan)}
     sched_bytes = D.ddl_plan_bytes_moved(w.plan)
-    D.ddl_plan_set_replay(w.plan, D.DDL_REPLAY_OFF)
+    D.ddl_plan_set_walk(w.plan, D.DDL_WALK_OFF)
     out["schedule"] = w.measure(D.ddl_allreduce_sim, K, W, nbytes=sched_bytes)
     out["learners_identical"] = bool(w.identical(W + K - 1))
+    D.ddl_plan_set_walk(w.plan, D.DDL_WALK_ON)
+    out["ring_walk_variant"] = w.measure(D.ddl_allreduce_sim, K, W, nbytes=D.ddl_plan_walk_bytes(w.plan))
+    out["learners_identical"] = out["learners_identical"] and bool(w.identical(W + K - 1))
     if sched_bytes / max(out["phases"], 1) < (64 << 20):
-        D.ddl_plan_set_replay(w.plan, D.DDL_REPLAY_ON)
-        out["schedule_graph_replay"] = w.measure(D.ddl_allreduce_sim, K, W, nbytes=sched_bytes)
         # back to back, no refills and no events between the calls: the launch-bound rate
         n = 200
         call = w.entry(D.ddl_allreduce_sim)
-        for mode, key in ((D.DDL_REPLAY_OFF, "eager"), (D.DDL_REPLAY_ON, "graph_replay")):
-            D.ddl_plan_set_replay(w.plan, mode)
+        for mode, key in ((D.DDL_WALK_OFF, "phases"), (D.DDL_WALK_ON, "ring_walk")):
+            D.ddl_plan_set_walk(w.plan, mode)
             for b in w.sets[0]:
                 b.zero_()
             call(0)
@@ -181,7 +182,7 @@ def secondary(torch, D, I, dev, cfg, K, W, budget_bytes):
                 call(0)
             torch.cuda.synchronize()
             out.setdefault("back_to_back_us", {})[key] = round((time.perf_counter() - t0) / n * 1e6, 2)
-    D.ddl_plan_set_replay(w.plan, D.DDL_REPLAY_AUTO)
+    D.ddl_plan_set_walk(w.plan, D.DDL_WALK_AUTO)
     try:
         out["fused_variant"] = w.measure(D.ddl_allreduce_fused_sim, K, W, nbytes=D.ddl_plan_fused_bytes(w.plan))
     except D.DdlError as e:
@@ -212,7 +213,7 @@ def box_sweep(torch, D, dev, P=256, iters=30, counts=(4096, 65536, 1 << 20), box
         for dims in boxes:
             plan = D.ddl_ring_plan(dims, P, count)
             D.ddl_plan_prepare(plan)
-            D.ddl_plan_set_replay(plan, D.DDL_REPLAY_OFF)
+            D.ddl_plan_set_walk(plan, D.DDL_WALK_OFF)
             for _ in range(3):
                 D.ddl_allreduce_sim(ptrs, P, plan, count, D.DDL_F32, stream)
             torch.cuda.synchronize()
@@ -227,9 +228,13 @@ def box_sweep(torch, D, dev, P=256, iters=30, counts=(4096, 65536, 1 << 20), box
     A = np.array([[r["phases"], r["bytes"]] for r in rows], dtype=np.float64)
     y = np.array([r["us"] * 1e-6 for r in rows])
     (L, invB), *_ = np.linalg.lstsq(A, y, rcond=None)
+    # The estimate charges S_t / (d_t * bw) per phase for ONE learner's transfer of 4-byte
+    # elements; here a phase is P such transfers through one memory, each element costing 12
+    # (reduce) or 8 (gather) bytes of traffic, 2.5 x 4 on average: bw = fitted rate / (2.5 P).
+    link_bw = 1.0 / invB / 2.5 / P
     picks = {}
     for count in counts:
-        dims, t = D.ddl_choose_dims(P, 4 * count, [1.0 / invB / 2.5] * 8, [float(L)] * 8)
+        dims, t = D.ddl_choose_dims(P, 4 * count, [link_bw] * 8, [float(L)] * 8)
         best = min((r for r in rows if r["count"] == count), key=lambda r: r["us"])
         mine = [r for r in rows if r["count"] == count and [d for d in r["dims"] if d > 1] == [d for d in dims if d > 1]]
         picks[str(count)] = {"chooser": [d for d in dims if d > 1], "modelled_us": round(t * 1e6, 1),
@@ -237,8 +242,8 @@ def box_sweep(torch, D, dev, P=256, iters=30, counts=(4096, 65536, 1 << 20), box
                              "fastest_measured": best["dims"], "fastest_us": best["us"]}
     return {"P": P, "iters": iters, "results": rows,
             "fit": {"latency_per_phase_us": round(L * 1e6, 3), "bandwidth_GBs": round(1e-9 / invB, 1),
-                    "note": "the chooser's per-link bandwidth is the fitted rate / 2.5: the model "
-                            "counts 4 bytes per element and transfer, the kernels move 12 or 8"},
+                    "note": "the chooser's per-link bandwidth is the fitted rate / (2.5 P): the model counts 4 "
+                            "bytes per element of one learner's transfer, a phase here is P transfers at 12 or 8"},
             "chooser": picks}
 
 
@@ -351,9 +356,20 @@ def main():
     nsteps = D.ddl_plan_num_steps(w.plan)
     bytes_total = D.ddl_plan_bytes_moved(w.plan)
 
-    # the schedule itself: `value`
+    # the schedule itself, phase by phase: `value`
+    D.ddl_plan_set_walk(w.plan, D.DDL_WALK_OFF)
     head = w.measure(D.ddl_allreduce_sim, K, W, nbytes=bytes_total)
     same = w.identical(W + K - 1)
+    # The same schedule with every dimension's phases walked in one launch: identical buffers,
+    # fewer bytes and launches; rated against its own bytes, reported beside `value`.
+    walk = None
+    if D.ddl_plan_walk_bytes(w.plan):
+        D.ddl_plan_set_walk(w.plan, D.DDL_WALK_ON)
+        walk = dict(entry="ddl_allreduce_sim with ddl_plan_set_walk(DDL_WALK_ON)",
+                    **w.measure(D.ddl_allreduce_sim, K, W, nbytes=D.ddl_plan_walk_bytes(w.plan)))
+        walk["speedup_vs_phases"] = head["ms_per_step"] / walk["ms_per_step"]
+        same = same and w.identical(W + K - 1)
+        D.ddl_plan_set_walk(w.plan, D.DDL_WALK_OFF)
     ms_per_step = head["ms_per_step"]
     per_learner_gbs = head["GBs_per_virtual_learner"]
 
@@ -435,6 +451,7 @@ def main():
         "learners_identical": bool(same),
         "device": device_info,
         "roofline": roofline,
+        "ring_walk_variant": walk,
         "fused_variant": fused,
         "per_tensor_variant": per_tensor,
         "other_configs": others,

@@ -115,19 +115,27 @@ ddl_status_t ddl_plan_prepare(const ddl_plan_t* plan);
 ddl_status_t ddl_plan_reserve_bindings(const ddl_plan_t* plan, int slots);
 
 /*
- * How ddl_allreduce_sim enqueues the phases of a plan whose tables are already bound to
- * the call's buffers: kernel by kernel, or as one launch of a graph recorded from those
- * same kernels (one graph per binding slot, recorded on the current device at first need).
- * The result is the same bit for bit; only the launch cost differs.
- *   DDL_REPLAY_AUTO (default)  graph from a binding's second use on, for plans whose
- *                              phases average under 16 MiB of traffic (launch-bound)
- *   DDL_REPLAY_OFF             always kernel by kernel
- *   DDL_REPLAY_ON              always the graph
- * Calls made while `stream` is being captured never use it (the caller's graph already
- * holds the kernels).
+ * Ring walk: how ddl_allreduce_sim, ddl_reduce_scatter_sim and ddl_allgather_sim execute the
+ * d-1 phases of one box dimension.  Phase by phase (one kernel launch per phase, the
+ * schedule as Sec. 4.3 states it), or as one launch per dimension in which every wave
+ * carries a piece of a chunk once round its ring: it loads the piece from all d positions,
+ * adds them in ring order and stores each partial sum where the phases would have left it
+ * (the gather loads once and stores d-1 times).  Every byte of every buffer ends up exactly
+ * as after the phases -- partial sums in the other learners' chunks included -- but the
+ * travelling partial sum is never read back from memory: (2d-1) + d memory accesses per
+ * element of a dimension's segment instead of 3(d-1) + 2(d-1), and 2 launches per dimension
+ * instead of 2(d-1).  A whole allreduce takes its last dimension's two halves in one launch
+ * (the sum goes straight to all d positions, 2d accesses: that dimension's gather would
+ * overwrite its own partial sums at once).  ddl_plan_walk_bytes gives the traffic of this form.
+ *   DDL_WALK_AUTO (default)  walk when the plan's phases average under 16 MiB of traffic
+ *                            (launch-bound: the saved phase boundaries dominate), else phases
+ *   DDL_WALK_OFF             always phase by phase
+ *   DDL_WALK_ON              always walk (DDL_ERR_UNSUPPORTED for a plan without the form:
+ *                            several tensors, or rings too long for its tables)
+ * The measurement entry points with an event per step always run phase by phase.
  */
-enum { DDL_REPLAY_AUTO = 0, DDL_REPLAY_OFF = 1, DDL_REPLAY_ON = 2 };
-ddl_status_t ddl_plan_set_replay(const ddl_plan_t* plan, int mode);
+enum { DDL_WALK_AUTO = 0, DDL_WALK_OFF = 1, DDL_WALK_ON = 2 };
+ddl_status_t ddl_plan_set_walk(const ddl_plan_t* plan, int mode);
 
 /*
  * In-place allreduce (Sec. 4.3: reduction R = sum_j V_j and its distribution to all
@@ -137,7 +145,8 @@ ddl_status_t ddl_plan_set_replay(const ddl_plan_t* plan, int mode);
  *          owned by the caller.  The array itself may be reused as soon as the call returns.
  *          With count == 0 the pointers are not examined (empty buffers may be NULL).
  *   P, count, dtype must equal the plan's.
- * Enqueues one kernel per step on `stream` and returns without synchronising; when the
+ * Enqueues one kernel per step (or per dimension, see ddl_plan_set_walk) on `stream` and
+ * returns without synchronising; when the
  * stream has drained, every bufs[j] holds the sum, bit-identical across learners, formed in
  * the order the schedule fixes: within the ring of dimension t the partial sum of part k
  * starts at ring position k+1 and is extended by positions k+2, ..., k+d_t (= k).
@@ -152,7 +161,7 @@ ddl_status_t ddl_plan_set_replay(const ddl_plan_t* plan, int mode);
  * another stream still reads it, which the caller must then order.  Slots allocate device
  * memory when they are created; see ddl_plan_prepare for callers that must avoid that.
  * A call under stream capture records its own binding kernel into the caller's graph and
- * keeps its slot for the plan's lifetime (replays stay valid whatever runs in between);
+ * keeps its slot for the plan's lifetime (replays of that graph stay valid whatever runs in between);
  * if no slot is free and none can be created it returns DDL_ERR_UNSUPPORTED.
  * Errors are reported before anything is enqueued, except DDL_ERR_HIP for a failed launch.
  */
@@ -272,6 +281,11 @@ size_t ddl_plan_bytes_moved(const ddl_plan_t* plan);
 /* Bytes ddl_allreduce_fused_sim moves: every element of every learner read once and
  * written once, plus one write and read of the result when it runs as two passes. */
 size_t ddl_plan_fused_bytes(const ddl_plan_t* plan);
+
+/* Bytes the ring-walk form of the whole allreduce moves (see ddl_plan_set_walk): per dimension
+ * of ring size d and element of its segment 2d-1 accesses reducing and d gathering, 2d in all
+ * for the last dimension.  0 for a plan without it. */
+size_t ddl_plan_walk_bytes(const ddl_plan_t* plan);
 
 /* ddl_plan_bytes_moved for one step; 0 for a bad index. */
 size_t ddl_plan_step_bytes(const ddl_plan_t* plan, int step);

@@ -12,9 +12,9 @@ _BINDING_NAMES = (
     "DDL_F32", "DDL_F64", "DDL_I32", "DDL_F16", "DDL_BF16",
     "DDL_OK", "DDL_ERR_ARG", "DDL_ERR_DIMS", "DDL_ERR_DTYPE", "DDL_ERR_ALIGN",
     "DDL_ERR_PLAN_MISMATCH", "DDL_ERR_NOMEM", "DDL_ERR_HIP", "DDL_ERR_UNSUPPORTED",
-    "DDL_STEP_REDUCE", "DDL_STEP_GATHER", "DDL_REPLAY_AUTO", "DDL_REPLAY_OFF", "DDL_REPLAY_ON",
+    "DDL_STEP_REDUCE", "DDL_STEP_GATHER", "DDL_WALK_AUTO", "DDL_WALK_OFF", "DDL_WALK_ON",
     "DdlError", "Plan",
-    "ddl_ring_plan", "ddl_ring_plan_tensors", "ddl_plan_free", "ddl_plan_prepare", "ddl_plan_reserve_bindings", "ddl_plan_set_replay",
+    "ddl_ring_plan", "ddl_ring_plan_tensors", "ddl_plan_free", "ddl_plan_prepare", "ddl_plan_reserve_bindings", "ddl_plan_set_walk", "ddl_plan_walk_bytes",
     "ddl_plan_num_tensors", "ddl_plan_owned_chunk_tensor",
     "ddl_assign_sim", "ddl_allreduce_sim", "ddl_allreduce_sim_noalloc", "ddl_reduce_scatter_sim", "ddl_allgather_sim",
     "ddl_allreduce_sim_profile", "ddl_allreduce_sim_timed", "ddl_allreduce_fused_sim", "ddl_reduce_scatter_fused_sim", "ddl_allgather_fused_sim",

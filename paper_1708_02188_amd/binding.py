@@ -9,7 +9,7 @@ DDL_OK = 0
 DDL_ERR_ARG, DDL_ERR_DIMS, DDL_ERR_DTYPE, DDL_ERR_ALIGN = -1, -2, -3, -4
 DDL_ERR_PLAN_MISMATCH, DDL_ERR_NOMEM, DDL_ERR_HIP, DDL_ERR_UNSUPPORTED = -5, -6, -7, -8
 DDL_STEP_REDUCE, DDL_STEP_GATHER = 0, 1
-DDL_REPLAY_AUTO, DDL_REPLAY_OFF, DDL_REPLAY_ON = 0, 1, 2
+DDL_WALK_AUTO, DDL_WALK_OFF, DDL_WALK_ON = 0, 1, 2
 
 
 def library_path():
@@ -47,7 +47,8 @@ def _load():
         "ddl_plan_free": (None, [vp]),
         "ddl_plan_prepare": (i, [vp]),
         "ddl_plan_reserve_bindings": (i, [vp, i]),
-        "ddl_plan_set_replay": (i, [vp, i]),
+        "ddl_plan_set_walk": (i, [vp, i]),
+        "ddl_plan_walk_bytes": (sz, [vp]),
         "ddl_allreduce_sim": (i, sim_args),
         "ddl_allreduce_sim_noalloc": (i, sim_args),
         "ddl_reduce_scatter_sim": (i, sim_args),
@@ -186,8 +187,12 @@ def ddl_plan_reserve_bindings(plan, slots):
     _check(_lib.ddl_plan_reserve_bindings(_h(plan), slots), "ddl_plan_reserve_bindings")
 
 
-def ddl_plan_set_replay(plan, mode):
-    _check(_lib.ddl_plan_set_replay(_h(plan), mode), "ddl_plan_set_replay")
+def ddl_plan_set_walk(plan, mode):
+    _check(_lib.ddl_plan_set_walk(_h(plan), mode), "ddl_plan_set_walk")
+
+
+def ddl_plan_walk_bytes(plan):
+    return _lib.ddl_plan_walk_bytes(_h(plan))
 
 
 def ddl_allreduce_sim(bufs, P, plan, count, dtype=DDL_F32, stream=None):

@@ -32,19 +32,19 @@ void release(T** d) {
 }
 
 void release_binding(ddl::Binding* b) {
-    if (b->replay) (void)hipGraphExecDestroy(static_cast<hipGraphExec_t>(b->replay));
     release(&b->rops);
     release(&b->items);
     release(&b->d_ptrs);
     release(&b->fused_ptrs);
+    release(&b->walk);
     delete b;
 }
 
 void release_tables(DeviceTables* t) {
     for (ddl::Binding* b : t->bindings) release_binding(b);
     t->bindings.clear();
-    if (t->capture_stream) (void)hipStreamDestroy(static_cast<hipStream_t>(t->capture_stream));
     release(&t->ops);
+    release(&t->walk_plan);
     release(&t->whole);
     release(&t->ragged);
     release(&t->fused_seq);
@@ -78,6 +78,7 @@ ddl_status_t device_tables_locked(const ddl_plan* plan, DeviceTables** out) {
     t->device = device;
     bool ok = true;
     if (!plan->ops.empty()) ok = upload(&t->ops, plan->ops);
+    if (ok && !plan->walk_plan.empty()) ok = upload(&t->walk_plan, plan->walk_plan);
     if (ok && !plan->whole.empty()) ok = upload(&t->whole, plan->whole);
     if (ok && !plan->ragged.empty()) ok = upload(&t->ragged, plan->ragged);
     if (!ok) {
@@ -124,6 +125,7 @@ ddl::Binding* new_binding(const ddl_plan* plan, const DeviceTables* t, bool fuse
     if (b == nullptr) return nullptr;
     bool ok = plan->ops.empty() || reserve(&b->rops, plan->ops.size());
     if (ok && !plan->whole.empty()) ok = reserve(&b->items, plan->whole.size());
+    if (ok && plan->walk_words) ok = reserve(&b->walk, plan->walk_words);
     if (ok && plan->P > ddl::kKernargLearners) ok = reserve(&b->d_ptrs, size_t(plan->P));
     if (ok && fused) ok = reserve(&b->fused_ptrs, size_t(plan->P) * size_t(t->fused_padded));
     if (!ok) {
@@ -175,7 +177,6 @@ ddl_status_t acquire_binding(void** bufs, int P, const ddl_plan* plan, hipStream
         }
         slot->key.assign(bufs, bufs + P);
         slot->rops_valid = slot->fused_valid = false;
-        slot->uses = 0;
     }
     if (fused && slot->fused_ptrs == nullptr) {
         if (capturing) return DDL_ERR_UNSUPPORTED;
@@ -198,6 +199,8 @@ ddl_status_t acquire_binding(void** bufs, int P, const ddl_plan* plan, hipStream
                                : ddl::launch_resolve(*plan, t->ops, slot->rops, table, d_ptrs, stream);
         if (err == hipSuccess && !fused)
             err = ddl::launch_resolve_items(*plan, slot->rops, t->whole, slot->items, stream);
+        if (err == hipSuccess && !fused && slot->walk)
+            err = ddl::launch_resolve_walk(*plan, t->walk_plan, slot->walk, table, d_ptrs, stream);
         if (err != hipSuccess) return DDL_ERR_HIP;
         if (capturing) slot->pinned = true;
         else if (fused) slot->fused_valid = true;
@@ -248,38 +251,35 @@ ddl_status_t launch_steps(const ddl_plan* plan, const DeviceTables* t, const ddl
 }
 
 // Phases shorter than this on average are launch-bound (a phase boundary costs the GPU
-// about as long as moving this many bytes): such plans replay their phases as a graph.
-constexpr uint64_t kReplayPhaseBytes = uint64_t(16) << 20;
+// about as long as moving this many bytes): such plans walk their rings by default.
+constexpr uint64_t kWalkPhaseBytes = uint64_t(16) << 20;
 
-bool wants_replay(const ddl_plan* plan, const ddl::Binding* slot) {
-    if (plan->replay_mode == DDL_REPLAY_OFF) return false;
-    if (plan->replay_mode == DDL_REPLAY_ON) return true;
-    return slot->uses >= 1 && plan->bytes_total / plan->steps.size() < kReplayPhaseBytes;
+bool wants_walk(const ddl_plan* plan) {
+    if (plan->walk_levels.empty() || plan->walk_mode == DDL_WALK_OFF) return false;
+    if (plan->walk_mode == DDL_WALK_ON) return true;
+    return plan->bytes_total / plan->steps.size() < kWalkPhaseBytes;
 }
 
-// The phases of the whole allreduce for one slot, recorded once as a graph.  The kernels
-// read the slot's table when they run, so the graph stays good when the slot is rebound.
-// Caller holds plan->mu.
-ddl_status_t build_replay(const ddl_plan* plan, DeviceTables* t, ddl::Binding* slot) {
-    if (t->capture_stream == nullptr) {
-        hipStream_t cs = nullptr;
-        if (hipStreamCreateWithFlags(&cs, hipStreamNonBlocking) != hipSuccess) return DDL_ERR_HIP;
-        t->capture_stream = cs;
-    }
-    hipStream_t cs = static_cast<hipStream_t>(t->capture_stream);
-    if (hipStreamBeginCapture(cs, hipStreamCaptureModeRelaxed) != hipSuccess) return DDL_ERR_HIP;
-    ddl_status_t st = launch_steps(plan, t, slot, 0, static_cast<int>(plan->steps.size()), cs, nullptr);
-    hipGraph_t graph = nullptr;
-    if (hipStreamEndCapture(cs, &graph) != hipSuccess || graph == nullptr) return DDL_ERR_HIP;
-    hipGraphExec_t exec = nullptr;
-    if (st == DDL_OK && hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0) != hipSuccess) st = DDL_ERR_HIP;
-    (void)hipGraphDestroy(graph);
-    if (st == DDL_OK) slot->replay = exec;
-    return st;
+// The reduce-scatter and / or the all-gather as ring walks: one launch per box dimension.
+ddl_status_t launch_walks(const ddl_plan* plan, const ddl::Binding* slot, bool reduce, bool gather,
+                          hipStream_t stream) {
+    const int levels = static_cast<int>(plan->walk_levels.size());
+    // a whole allreduce takes the last dimension's reduce-scatter and all-gather in one launch
+    const int both = reduce && gather ? levels - 1 : -1;
+    if (reduce)
+        for (int l = 0; l < levels; ++l)
+            if (ddl::launch_walk(*plan, plan->walk_levels[l], slot->walk, l == both ? 2 : 1, stream) != hipSuccess)
+                return DDL_ERR_HIP;
+    if (gather)
+        for (int l = levels - 1; l >= 0; --l)
+            if (l != both && ddl::launch_walk(*plan, plan->walk_levels[l], slot->walk, 0, stream) != hipSuccess)
+                return DDL_ERR_HIP;
+    return DDL_OK;
 }
 
 // Run steps [first, last) of the plan.  events: NULL, or last-first+1 created events that
-// are recorded round every launch.
+// are recorded round every launch.  Ranges that are the whole reduce-scatter, the whole
+// all-gather or both may run as ring walks (see ddl_plan_set_walk); the buffers end up the same.
 ddl_status_t run_steps(void** bufs, int P, const ddl_plan* plan, size_t count, ddl_dtype_t dtype,
                        void* stream_v, int first, int last, hipEvent_t* events) {
     ddl_status_t st = check_call(bufs, P, plan, count, dtype);
@@ -293,22 +293,16 @@ ddl_status_t run_steps(void** bufs, int P, const ddl_plan* plan, size_t count, d
     st = acquire_binding(bufs, P, plan, stream, false, &t, &slot, &was_bound);
     if (st != DDL_OK) return st;
     if (events && hipEventRecord(events[0], stream) != hipSuccess) return DDL_ERR_HIP;
-    const bool whole = first == 0 && last == static_cast<int>(plan->steps.size()) && events == nullptr;
-    if (whole && !stream_is_capturing(stream)) {
-        hipGraphExec_t exec = nullptr;
-        {
-            std::lock_guard<std::mutex> lock(plan->mu);
-            if (wants_replay(plan, slot)) {
-                if (slot->replay == nullptr) {
-                    st = build_replay(plan, t, slot);
-                    if (st != DDL_OK) return st;
-                }
-                exec = static_cast<hipGraphExec_t>(slot->replay);
-            }
-            if (was_bound) ++slot->uses;
-        }
-        if (exec != nullptr) return hipGraphLaunch(exec, stream) == hipSuccess ? DDL_OK : DDL_ERR_HIP;
+    const int steps = static_cast<int>(plan->steps.size());
+    const bool reduce = first == 0 && last >= plan->first_gather;
+    const bool gather = last == steps && first <= plan->first_gather;
+    const bool halves = (first == 0 || first == plan->first_gather) && (last == steps || last == plan->first_gather);
+    bool walk;
+    {
+        std::lock_guard<std::mutex> lock(plan->mu);
+        walk = events == nullptr && halves && first < last && slot->walk != nullptr && wants_walk(plan);
     }
+    if (walk) return launch_walks(plan, slot, reduce, gather, stream);
     return launch_steps(plan, t, slot, first, last, stream, events);
 }
 
@@ -351,6 +345,7 @@ ddl_plan_t* make_plan(const int* dims, int m, int P, const size_t* seg_off, cons
         plan->seg_off.assign(seg_off, seg_off + S);
         plan->seg_count.assign(seg_count, seg_count + S);
         ddl::build_schedule(plan);
+        ddl::build_walk(plan);
     } catch (const std::bad_alloc&) {
         delete plan;
         set_status(status, DDL_ERR_NOMEM);
@@ -428,10 +423,11 @@ ddl_status_t ddl_plan_prepare(const ddl_plan_t* plan) { return prepare(plan, 2);
 
 ddl_status_t ddl_plan_reserve_bindings(const ddl_plan_t* plan, int slots) { return prepare(plan, slots); }
 
-ddl_status_t ddl_plan_set_replay(const ddl_plan_t* plan, int mode) {
-    if (plan == nullptr || mode < DDL_REPLAY_AUTO || mode > DDL_REPLAY_ON) return DDL_ERR_ARG;
+ddl_status_t ddl_plan_set_walk(const ddl_plan_t* plan, int mode) {
+    if (plan == nullptr || mode < DDL_WALK_AUTO || mode > DDL_WALK_ON) return DDL_ERR_ARG;
+    if (mode == DDL_WALK_ON && plan->walk_levels.empty() && !plan->steps.empty()) return DDL_ERR_UNSUPPORTED;
     std::lock_guard<std::mutex> lock(plan->mu);
-    plan->replay_mode = mode;
+    plan->walk_mode = mode;
     return DDL_OK;
 }
 
@@ -609,6 +605,8 @@ size_t ddl_plan_fused_bytes(const ddl_plan_t* plan) {
     const size_t per_elem = plan->P >= DDL_FUSED_TWO_PASS_FROM ? size_t(2) * plan->P + 2 : size_t(2) * plan->P;
     return per_elem * plan->elem_size * plan->count;
 }
+
+size_t ddl_plan_walk_bytes(const ddl_plan_t* plan) { return plan ? plan->walk_bytes : 0; }
 
 size_t ddl_plan_step_bytes(const ddl_plan_t* plan, int step) {
     if (plan == nullptr || step < 0 || step >= static_cast<int>(plan->steps.size())) return 0;

@@ -630,7 +630,172 @@ hipError_t launch_fused_typed(const ddl_plan& plan, const DeviceTables& t, const
     return hipGetLastError();
 }
 
+// ---------------------------------------------------------------------------------------
+// Ring walk: all d-1 phases of one box dimension in one launch
+// ---------------------------------------------------------------------------------------
+// During the d-1 reduce-scatter phases of a dimension every chunk travels once round its
+// ring: it sets out from the position after its owner and each next position adds its own
+// copy and stores the sum (Sec. 4.3: d-1 phases of d concurrent transfers).  One wave can
+// carry a row of the chunk along that whole path: it loads the row from all d positions,
+// adds them in ring order and stores every partial sum where the phases would have left
+// it.  The memory state after the launch is the phases' state bit for bit, but the partial
+// sum is never read back: (2d-1) accesses per element instead of 3(d-1).  The gather is the
+// same walk with one load and d-1 stores (d accesses instead of 2(d-1)).
+// Rows of the table: length n, then the chunk's address at the d positions in ring order.
+__global__ __launch_bounds__(256) void resolve_walk(const PtrTable table, void* const* __restrict__ d_ptrs,
+                                                    const uint64_t* __restrict__ plan_rows,
+                                                    uint64_t* __restrict__ out, unsigned rows, unsigned d,
+                                                    unsigned elem_size) {
+    const unsigned i = blockIdx.x * 256u + threadIdx.x;
+    if (i >= rows) return;
+    const uint64_t* in = plan_rows + size_t(i) * (d + 2);
+    uint64_t* o = out + size_t(i) * (d + 1);
+    const uint64_t byte_off = in[0] * elem_size;
+    o[0] = in[1];
+    for (unsigned k = 0; k < d; ++k) {
+        const uint64_t r = in[2 + k];
+        o[1 + k] = reinterpret_cast<uint64_t>(d_ptrs ? d_ptrs[r] : table.p[r]) + byte_off;
+    }
+}
+
+#ifndef DDL_WALK_ROWS
+#define DDL_WALK_ROWS 2
+#endif
+constexpr int kWalkBatch = 8;   // ring positions whose rows a wave loads before it adds and stores
+
+// What a walk does at every place of a chunk.  WALK_BOTH serves the last dimension of a whole
+// allreduce: its gather overwrites the partial sums of its own reduce-scatter at once, so the
+// sum is formed in ring order and stored to all d positions (2d accesses per element).
+enum { WALK_GATHER = 0, WALK_REDUCE = 1, WALK_BOTH = 2 };
+
+template <typename T, typename X, int MODE>
+__device__ __forceinline__ void walk_place(const DDL_CONST uint64_t* addr, int d, uint64_t byte_off) {
+    X acc = *(const DDL_GLOBAL X*)(addr[0] + byte_off);
+    for (int i = 1; i < d; ++i) {
+        DDL_GLOBAL X* p = (DDL_GLOBAL X*)(addr[i] + byte_off);
+        if (MODE != WALK_GATHER) acc = Elem<T>::sum(*p, acc);
+        if (MODE != WALK_BOTH) *p = acc;
+    }
+    if (MODE == WALK_BOTH)
+        for (int i = 0; i < d; ++i) *(DDL_GLOBAL X*)(addr[i] + byte_off) = acc;
+}
+
+template <typename T, int MODE>
+__global__ __launch_bounds__(64) void walk_kernel(const uint64_t* table_, int d, unsigned tile_stride) {
+    typedef typename Elem<T>::V V;
+    typedef typename Elem<T>::S S;
+    constexpr int64_t VL = 16 / sizeof(S);
+    constexpr int R = MODE == WALK_GATHER ? 1 : DDL_WALK_ROWS;
+    constexpr int64_t kTileVecs = int64_t(R) * 64;
+    const DDL_CONST uint64_t* row = (const DDL_CONST uint64_t*)table_ + size_t(blockIdx.y) * (d + 1);
+    const int64_t n = int64_t(row[0]);
+    const DDL_CONST uint64_t* addr = row + 1;
+    const int64_t nv = n / VL;
+    // rows on absolute 1 KiB boundaries of the chunk at its last position (the owner of a
+    // reduced chunk; every learner's copy has the same offset within its buffer)
+    const int64_t shift = int64_t((addr[d - 1] % kRowBytes) / 16);
+    const int64_t lane = threadIdx.x;
+    for (int64_t tile = int64_t(blockIdx.x) * kTileVecs - shift; tile <= nv; tile += int64_t(tile_stride) * kTileVecs) {
+        if (tile >= 0 && tile + kTileVecs <= nv) {
+            const uint64_t byte_off = uint64_t(tile + lane) * 16;
+            V acc[R];
+#pragma unroll
+            for (int r = 0; r < R; ++r) acc[r] = stream_load((const DDL_GLOBAL V*)(addr[0] + byte_off) + r * 64);
+            if (MODE != WALK_GATHER) {
+                for (int i0 = 1; i0 < d; i0 += kWalkBatch) {
+                    V x[kWalkBatch][R];
+#pragma unroll
+                    for (int j = 0; j < kWalkBatch; ++j)
+                        if (i0 + j < d) {
+#pragma unroll
+                            for (int r = 0; r < R; ++r)
+                                x[j][r] = stream_load((const DDL_GLOBAL V*)(addr[i0 + j] + byte_off) + r * 64);
+                        }
+#pragma unroll
+                    for (int j = 0; j < kWalkBatch; ++j)
+                        if (i0 + j < d) {
+#pragma unroll
+                            for (int r = 0; r < R; ++r) {
+                                acc[r] = Elem<T>::sum(x[j][r], acc[r]);
+                                if (MODE == WALK_REDUCE)
+                                    stream_store((DDL_GLOBAL V*)(addr[i0 + j] + byte_off) + r * 64, acc[r]);
+                            }
+                        }
+                }
+            }
+            if (MODE != WALK_REDUCE) {
+                for (int i = MODE == WALK_BOTH ? 0 : 1; i < d; ++i) {
+#pragma unroll
+                    for (int r = 0; r < R; ++r) gather_store((DDL_GLOBAL V*)(addr[i] + byte_off) + r * 64, acc[r]);
+                }
+            }
+        } else {
+            // first or last rows of the chunk: per-lane bounds
+            for (int r = 0; r < R; ++r) {
+                const int64_t v = tile + r * 64 + lane;
+                if (v >= 0 && v < nv) {
+                    walk_place<T, V, MODE>(addr, d, uint64_t(v) * 16);
+                } else if (v == nv) {
+                    // the buffer's last, short vector: element by element
+                    for (int64_t e = nv * VL; e < n; ++e) walk_place<T, S, MODE>(addr, d, uint64_t(e) * sizeof(S));
+                }
+            }
+        }
+    }
+}
+
+template <typename T>
+hipError_t launch_walk_typed(const ddl_plan& plan, const WalkLevel& level, const uint64_t* d_rows, int mode,
+                             hipStream_t stream) {
+    constexpr uint64_t VL = 16 / sizeof(typename Elem<T>::S);
+    const uint64_t tile_vecs = uint64_t(mode == WALK_GATHER ? 1 : DDL_WALK_ROWS) * 64;
+    uint64_t tiles = (level.max_n / VL + 1 + (kRowVecs - 1) + tile_vecs - 1) / tile_vecs;
+    const uint64_t max_x = (DDL_MAX_GRID_THREADS / 64 - 1) / uint64_t(plan.P);
+    if (tiles > max_x) tiles = max_x;
+    if (tiles == 0) tiles = 1;
+    const dim3 grid(static_cast<unsigned>(tiles), static_cast<unsigned>(plan.P), 1);
+    // the reduce rows list each chunk's positions from the one after its owner to the owner
+    if (mode == WALK_REDUCE)
+        hipLaunchKernelGGL((walk_kernel<T, WALK_REDUCE>), grid, dim3(64), 0, stream, d_rows + level.reduce_rows,
+                           level.d, grid.x);
+    else if (mode == WALK_BOTH)
+        hipLaunchKernelGGL((walk_kernel<T, WALK_BOTH>), grid, dim3(64), 0, stream, d_rows + level.reduce_rows,
+                           level.d, grid.x);
+    else
+        hipLaunchKernelGGL((walk_kernel<T, WALK_GATHER>), grid, dim3(64), 0, stream, d_rows + level.gather_rows,
+                           level.d, grid.x);
+    return hipGetLastError();
+}
+
 }  // namespace
+
+hipError_t launch_resolve_walk(const ddl_plan& plan, const uint64_t* d_walk_plan, uint64_t* d_rows,
+                               const PtrTable& table, void* const* d_ptrs, hipStream_t stream) {
+    for (const WalkLevel& level : plan.walk_levels)
+        for (int half = 0; half < 2; ++half) {
+            const unsigned rows = static_cast<unsigned>(plan.P);
+            hipLaunchKernelGGL(resolve_walk, dim3((rows + 255) / 256), dim3(256), 0, stream, table, d_ptrs,
+                               d_walk_plan + (half == 0 ? level.reduce_plan : level.gather_plan),
+                               d_rows + (half == 0 ? level.reduce_rows : level.gather_rows), rows,
+                               unsigned(level.d), unsigned(plan.elem_size));
+            const hipError_t err = hipGetLastError();
+            if (err != hipSuccess) return err;
+        }
+    return hipSuccess;
+}
+
+hipError_t launch_walk(const ddl_plan& plan, const WalkLevel& level, const uint64_t* d_rows, int mode,
+                       hipStream_t stream) {
+    if (level.max_n == 0) return hipSuccess;
+    switch (plan.dtype) {
+        case DDL_F32: return launch_walk_typed<float>(plan, level, d_rows, mode, stream);
+        case DDL_F64: return launch_walk_typed<double>(plan, level, d_rows, mode, stream);
+        case DDL_I32: return launch_walk_typed<unsigned>(plan, level, d_rows, mode, stream);
+        case DDL_F16: return launch_walk_typed<_Float16>(plan, level, d_rows, mode, stream);
+        case DDL_BF16: return launch_walk_typed<bf16_bits>(plan, level, d_rows, mode, stream);
+    }
+    return hipErrorInvalidValue;
+}
 
 hipError_t launch_store_pointers(void* const* bufs, int P, void** d_ptrs, hipStream_t stream) {
     for (int first = 0; first < P; first += kKernargLearners) {

@@ -127,6 +127,57 @@ void build_schedule(ddl_plan* plan) {
         for (int phase = 0; phase + 1 < plan->dims[t]; ++phase) emit(DDL_STEP_GATHER, t, phase);
 }
 
+void build_walk(ddl_plan* plan) {
+    plan->walk_levels.clear();
+    plan->walk_plan.clear();
+    plan->walk_words = 0;
+    plan->walk_bytes = 0;
+    if (plan->seg_off.size() != 1 || plan->steps.empty()) return;
+    const int P = plan->P;
+    size_t words = 0;
+    for (int d : plan->dims)
+        if (d > 1) words += 2 * size_t(P) * (size_t(d) + 2);
+    if (words > kWalkMaxWords) return;
+    // first phase of every dimension's reduce-scatter and all-gather in the step list
+    std::vector<int> first_reduce(plan->dims.size(), -1), first_gather(plan->dims.size(), -1);
+    for (int s = static_cast<int>(plan->steps.size()) - 1; s >= 0; --s) {
+        const Step& st = plan->steps[s];
+        (st.kind == DDL_STEP_REDUCE ? first_reduce : first_gather)[st.dim] = s;
+    }
+    for (size_t t = 0; t < plan->dims.size(); ++t) {
+        const int d = plan->dims[t];
+        if (d <= 1) continue;
+        WalkLevel level{int(t), d, 0, 0, 0, 0, 0};
+        for (int half = 0; half < 2; ++half) {
+            const int s0 = half == 0 ? first_reduce[t] : first_gather[t];
+            (half == 0 ? level.reduce_plan : level.gather_plan) = plan->walk_plan.size();
+            (half == 0 ? level.reduce_rows : level.gather_rows) = plan->walk_words;
+            plan->walk_words += size_t(P) * (size_t(d) + 1);
+            for (int r = 0; r < P; ++r) {
+                // the chunk that learner r passes on in the dimension's first phase keeps its
+                // range through all d-1 phases; its path is r, next(r), next(next(r)), ...
+                const Op& op0 = plan->ops[size_t(s0) * P + r];
+                plan->walk_plan.push_back(op0.off);
+                plan->walk_plan.push_back(op0.n);
+                int at = r;
+                for (int i = 0; i < d; ++i) {
+                    plan->walk_plan.push_back(uint64_t(at));
+                    if (i + 1 < d) at = plan->ops[size_t(s0 + i) * P + at].dst;
+                }
+                if (op0.n > level.max_n) level.max_n = op0.n;
+                // reduce: d reads and d-1 writes of the chunk; gather: 1 read and d-1 writes;
+                // the last dimension of the allreduce does both at once: d reads, d writes
+                int last = -1;
+                for (size_t u = 0; u < plan->dims.size(); ++u)
+                    if (plan->dims[u] > 1) last = int(u);
+                const int accesses = int(t) == last ? (half == 0 ? 2 * d : 0) : (half == 0 ? 2 * d - 1 : d);
+                plan->walk_bytes += op0.n * uint64_t(plan->elem_size) * uint64_t(accesses);
+            }
+        }
+        plan->walk_levels.push_back(level);
+    }
+}
+
 int build_fused_order(const ddl_plan& plan, std::vector<uint32_t>* seq, std::vector<uint32_t>* ctl,
                       int* padded) {
     // Rings of size 1 add nothing; the others are the levels, dimension 1 innermost.

@@ -84,15 +84,25 @@ struct Binding {
     uint64_t* fused_ptrs = nullptr;   // step-fused path: P * padded absolute addresses (on demand)
     bool rops_valid = false;          // an eager call has enqueued the kernel that fills rops for `key`
     bool fused_valid = false;         // the same for fused_ptrs
+    uint64_t* walk = nullptr;         // ring-walk rows bound to these buffers (plans that have them)
     bool pinned = false;              // a captured graph refers to this slot: it is never rebound
     uint64_t last_use = 0;
-    uint64_t uses = 0;                // eager whole-allreduce calls that found the slot bound
-    void* replay = nullptr;           // hipGraphExec_t: the phases of the whole allreduce as one graph
+};
+
+// One box dimension of size d > 1 walked in a single launch (see build_walk): `reduce` / `gather`
+// index the first of P rows in the plan's walk table and in a binding's resolved copy.
+struct WalkLevel {
+    int dim;              // 0-based box dimension
+    int d;                // ring size
+    uint64_t max_n;       // longest chunk (sizes the launch)
+    size_t reduce_plan, gather_plan;   // rows of d + 2 words: element offset, length, the d ring members in order
+    size_t reduce_rows, gather_rows;   // rows of d + 1 words: length, then the chunk's d addresses in ring order
 };
 
 struct DeviceTables {
     int device = -1;
     Op* ops = nullptr;           // num_steps * P operations, step-major
+    uint64_t* walk_plan = nullptr;   // ring-walk rows (learner indices), see WalkLevel
     BlockDesc* whole = nullptr;   // work lists of a several-tensor plan
     BlockDesc* ragged = nullptr;
     // step-fused path, created at its first use
@@ -104,7 +114,6 @@ struct DeviceTables {
     int fused_padded = 0;             // row length of fused_seq / fused_ptrs
     std::vector<Binding*> bindings;
     uint64_t clock = 0;               // orders the bindings' last uses
-    void* capture_stream = nullptr;   // hipStream_t on which replay graphs are recorded
 };
 
 }  // namespace ddl
@@ -122,10 +131,14 @@ struct ddl_plan {
     std::vector<ddl::BlockDesc> whole, ragged;  // work lists, only when S > 1
     std::vector<uint64_t> own_off, own_n; // finest chunk per (tensor, learner)
     uint64_t bytes_total = 0;
+    std::vector<ddl::WalkLevel> walk_levels;   // empty: the plan has no ring-walk form
+    std::vector<uint64_t> walk_plan;           // rows of all levels (learner indices)
+    size_t walk_words = 0;                     // size of a binding's resolved copy
+    uint64_t walk_bytes = 0;                   // memory traffic of the ring-walk form
 
     mutable std::mutex mu;                       // guards `tables` and everything below them
     mutable std::vector<ddl::DeviceTables*> tables;  // one entry per device the plan ran on
-    mutable int replay_mode = 0;                 // DDL_REPLAY_AUTO / _OFF / _ON
+    mutable int walk_mode = 0;                   // DDL_WALK_AUTO / _OFF / _ON
 };
 
 namespace ddl {
@@ -138,6 +151,15 @@ void split_range(uint64_t lo, uint64_t hi, uint64_t d, uint64_t k, uint64_t G,
 
 // Fills `plan` (dims, P, count, dtype already validated by the caller).
 void build_schedule(ddl_plan* plan);
+
+// Ring-walk form of a single-tensor plan, derived from its phases (call after build_schedule):
+// the d-1 phases of a dimension's reduce-scatter pass every chunk once round its ring, so one
+// launch can carry each chunk's partial sum from the position after its owner to the owner,
+// storing it at every position on the way exactly as the phases do; likewise the d-1 gather
+// phases copy every completed chunk from its owner to the other d-1 positions.  Leaves the
+// plan without the form if its tables would exceed kWalkMaxWords.
+constexpr size_t kWalkMaxWords = size_t(1) << 22;
+void build_walk(ddl_plan* plan);
 
 ddl_status_t validate_dims(const int* dims, int m, int P);
 

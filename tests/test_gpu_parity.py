@@ -449,28 +449,72 @@ def test_more_buffer_sets_than_binding_slots(dev):
     assert e.value.status == D.DDL_ERR_ARG
 
 
-@pytest.mark.parametrize("mode", ["auto", "on", "off"])
-def test_graph_replay_of_the_phases_gives_the_same_bits(dev, mode):
-    """Launch-bound plans replay their phases as one graph per binding slot; repeated calls,
-    alternating buffer sets and eager work in between must all give the eager result."""
+WALK_CASES = [([4], 1 << 16, D.DDL_F32), ([4], 37, D.DDL_F32), ([2], 1, D.DDL_F32), ([3], 100003, D.DDL_F32),
+              ([2, 3], 50001, D.DDL_F32), ([4, 4], 300007, D.DDL_F32), ([3, 1, 2], 70001, D.DDL_F32),
+              ([4, 8, 8], 300001, D.DDL_F32), ([4, 8, 8], 1000, D.DDL_F32), ([16], 150001, D.DDL_F32),
+              ([20, 2], 99999, D.DDL_F32), ([7, 3], 123457, D.DDL_F64), ([4, 2, 2], 262144 + 13, D.DDL_BF16),
+              ([5, 2], 65537, D.DDL_F16), ([9], 4099, D.DDL_I32), ([1, 1], 500, D.DDL_F32), ([2, 2], 0, D.DDL_F32)]
+
+
+@pytest.mark.parametrize("dims,count,dtype", WALK_CASES)
+def test_ring_walk_leaves_every_buffer_as_the_phases_do(dev, dims, count, dtype):
+    """One launch per dimension instead of one per phase: after the reduce-scatter every
+    learner's whole buffer (partial sums in the chunks it does not own included), after the
+    all-gather and after the whole allreduce must equal the step simulator's bit for bit."""
+    P = prod(dims)
+    say(f"ring walk dims={dims} count={count} dtype={dtype}")
+    rng = np.random.default_rng(300 + count + P)
+    V = wide_inputs(rng, P, count, dtype)
+    add = O.bf16_add if dtype == D.DDL_BF16 else None
+    plan = D.ddl_ring_plan(dims, P, count, dtype)
+    D.ddl_plan_set_walk(plan, D.DDL_WALK_ON)
+    with np.errstate(over="ignore"):
+        want_rs = O.reduce_scatter_steps(V, dims, add=add)
+        want = O.allgather_steps(want_rs, dims)
+    bufs = upload(V, dev)
+    D.ddl_reduce_scatter_sim(bufs, P, plan, count, dtype)
+    for j, g in enumerate(download(bufs, NP_OF[dtype])):
+        assert_bitwise(g, want_rs[j], f"walk reduce-scatter learner={j}")
+    D.ddl_allgather_sim(bufs, P, plan, count, dtype)
+    for j, g in enumerate(download(bufs, NP_OF[dtype])):
+        assert_bitwise(g, want[j], f"walk all-gather learner={j}")
+    bufs = upload(V, dev)
+    D.ddl_allreduce_sim(bufs, P, plan, count, dtype)
+    for j, g in enumerate(download(bufs, NP_OF[dtype])):
+        assert_bitwise(g, want[j], f"walk allreduce learner={j}")
+    if count:
+        assert 0 < D.ddl_plan_walk_bytes(plan) < D.ddl_plan_bytes_moved(plan) or P == 1 or max(dims) == 2
+
+
+def test_ring_walk_modes_and_limits(dev):
+    """AUTO walks launch-bound plans only; the result never depends on the mode; plans without
+    the form refuse DDL_WALK_ON."""
     dims, P, count = [4, 2, 2], 16, 20011
     rng = np.random.default_rng(91)
-    plan = D.ddl_ring_plan(dims, P, count)
-    D.ddl_plan_set_replay(plan, {"auto": D.DDL_REPLAY_AUTO, "on": D.DDL_REPLAY_ON, "off": D.DDL_REPLAY_OFF}[mode])
-    Vs = [[(rng.uniform(-1, 1, count) * 1e-3).astype(np.float32) for _ in range(P)] for _ in range(2)]
-    sets = [upload(V, dev) for V in Vs]
-    want = [[v.copy() for v in V] for V in Vs]
-    stream = torch.cuda.current_stream()
-    for call in range(6):
-        k = call % 2 if call < 4 else 0
-        say(f"replay mode {mode}: call {call} on set {k}")
-        D.ddl_allreduce_sim(sets[k], P, plan, count, D.DDL_F32, stream)
-        want[k] = O.allreduce_steps(want[k], dims)
-        for j, g in enumerate(download(sets[k])):
-            assert_bitwise(g, want[k][j], f"mode {mode} call {call} learner={j}")
-        sets[k][0].add_(0.0)   # eager work between the calls
+    V = wide_inputs(rng, P, count, D.DDL_F32)
+    want = O.allreduce_steps(V, dims)
+    for mode in (D.DDL_WALK_AUTO, D.DDL_WALK_OFF, D.DDL_WALK_ON):
+        plan = D.ddl_ring_plan(dims, P, count)
+        D.ddl_plan_set_walk(plan, mode)
+        bufs = upload(V, dev)
+        for _ in range(2):
+            D.ddl_allreduce_sim(bufs, P, plan, count)
+        want2 = O.allreduce_steps(want, dims)
+        for j, g in enumerate(download(bufs)):
+            assert_bitwise(g, want2[j], f"mode {mode} learner={j}")
+        # the measurement entries run phase by phase whatever the mode
+        bufs = upload(V, dev)
+        ms = D.ddl_allreduce_sim_profile(bufs, P, plan, count)
+        assert len(ms) == 10 and all(x > 0 for x in ms)
+        for j, g in enumerate(download(bufs)):
+            assert_bitwise(g, want[j], f"profile mode {mode} learner={j}")
     with pytest.raises(D.DdlError):
-        D.ddl_plan_set_replay(plan, 7)
+        D.ddl_plan_set_walk(plan, 7)
+    tplan = D.ddl_ring_plan_tensors([2, 2], 4, [0, 512], [100, 512], 1024)
+    with pytest.raises(D.DdlError) as e:
+        D.ddl_plan_set_walk(tplan, D.DDL_WALK_ON)
+    assert e.value.status == D.DDL_ERR_UNSUPPORTED
+    assert D.ddl_plan_walk_bytes(tplan) == 0
 
 
 def test_capture_with_more_learners_than_the_kernarg_table(dev):
@@ -538,6 +582,61 @@ def test_more_learners_than_the_kernarg_table_holds(dev):
         assert_bitwise(got[j], want, f"learner={j}")
 
 
+# ---------------------------------------------------------------------------------------
+# dimension chooser and cost estimate on the GPU machine
+# ---------------------------------------------------------------------------------------
+def test_chooser_and_estimate_equal_the_oracle_on_this_box():
+    """The host-only chooser / estimate checks, run on the GPU machine as well."""
+    import test_library_host as H
+    H.test_model_time_matches_oracle_and_paper_figures()
+    H.test_choose_dims_matches_bruteforce_oracle()
+
+
+def test_chooser_fed_with_measured_latency_and_rate_picks_a_fast_box(dev):
+    """Sec. 4.3's trade-off on one GPU: the latency of a phase is a launch boundary, the
+    bandwidth is the memory's.  Time three boxes of 64 learners on one buffer size, fit
+    T = phases * L + bytes / B, feed the estimate with the fit: the box ddl_choose_dims
+    picks must be within 10 % of the fastest box measured."""
+    import time
+    P, count = 64, 16384
+    bufs = [torch.zeros(count, dtype=torch.float32, device=dev) for _ in range(P)]
+    ptrs = D.pointer_array(bufs)
+    stream = torch.cuda.current_stream()
+
+    def measure(dims, reps=7, iters=40):
+        plan = D.ddl_ring_plan(dims, P, count)
+        D.ddl_plan_prepare(plan)
+        D.ddl_plan_set_walk(plan, D.DDL_WALK_OFF)
+        times = []
+        for rep in range(reps + 1):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(iters):
+                D.ddl_allreduce_sim(ptrs, P, plan, count, D.DDL_F32, stream)
+            torch.cuda.synchronize()
+            if rep:   # the first repetition warms up
+                times.append((time.perf_counter() - t0) / iters)
+        return sorted(times)[len(times) // 2], D.ddl_plan_num_steps(plan), D.ddl_plan_bytes_moved(plan)
+
+    boxes = [[64], [8, 8], [4, 4, 4]]
+    rows = [measure(b) for b in boxes]
+    A = np.array([[ph, by] for _, ph, by in rows], dtype=np.float64)
+    y = np.array([t for t, _, _ in rows])
+    (L, invB), *_ = np.linalg.lstsq(A, y, rcond=None)
+    say(f"  measured us: {[round(t * 1e6, 1) for t, _, _ in rows]} for {boxes}; fit L = {L * 1e6:.2f} us per phase, "
+        f"B = {1e-9 / invB if invB > 0 else float('inf'):.0f} GB/s")
+    assert 0.5e-6 < L < 20e-6, "a phase boundary costs microseconds"
+    link_bw = (1.0 / invB if invB > 0 else 1e15) / 2.5 / P
+    dims, modelled = D.ddl_choose_dims(P, 4 * count, [link_bw] * 6, [float(L)] * 6)
+    picked = [d for d in dims if d > 1]
+    t_pick, phases, _ = measure(picked)
+    fastest = min(min(t for t, _, _ in rows), t_pick)
+    say(f"  chooser picks {picked} ({phases} phases): measured {t_pick * 1e6:.1f} us, modelled {modelled * 1e6:.1f} us, "
+        f"fastest measured {fastest * 1e6:.1f} us")
+    assert t_pick <= 1.10 * fastest
+    assert phases <= min(ph for _, ph, _ in rows)   # latency-bound size: fewest phases win
+
+
 STRIDE_PATHS_CHILD = r"""
 import sys
 from math import prod
@@ -560,10 +659,13 @@ for dims, count in (([4, 4], 1_000_003), ([2], 300_001), ([4, 8, 8], 300_001)):
     P = prod(dims)
     V = [(rng.uniform(-1, 1, count) * 10.0 ** rng.uniform(-3, 3, count)).astype(np.float32) for _ in range(P)]
     plan = D.ddl_ring_plan(dims, P, count)
+    D.ddl_plan_set_walk(plan, D.DDL_WALK_OFF)
     want = O.allreduce_fold(V, dims)
     b = up(V); D.ddl_allreduce_sim(b, P, plan, count); check(b, want, f"phases {dims} {count}")
     b = up(V); D.ddl_allreduce_fused_sim(b, P, plan, count); check(b, want, f"fused {dims} {count}")
     b = up(V); D.ddl_allreduce_sim_noalloc(b, P, plan, count); check(b, want, f"noalloc {dims} {count}")
+    D.ddl_plan_set_walk(plan, D.DDL_WALK_ON)
+    b = up(V); D.ddl_allreduce_sim(b, P, plan, count); check(b, want, f"ring walk {dims} {count}")
 # 16-bit elements
 dims, count, P = [3, 2], 700_001, 6
 V = [O.f32_to_bf16(rng.uniform(-1, 1, count).astype(np.float32)) for _ in range(P)]
@@ -820,14 +922,18 @@ def compare_whole(results, dims, seed, dist, tensors, what):
     import time
     from concurrent.futures import ThreadPoolExecutor
 
-    tasks = [(off, n, a, min(n, a + PIECE)) for off, n in tensors for a in range(0, n, PIECE)]
     P = prod(dims)
+    # A tensor short enough that its finest chunks are tiny is cheaper by the step simulator,
+    # whole (one task, P * n * 4 bytes of inputs); the nested fold would make P x P small reads.
+    short = 8192 * P // 2
+    tasks = [(off, n, a, min(n, a + PIECE)) for off, n in tensors if n > short for a in range(0, n, PIECE)]
+    tasks += [(off, n, 0, n) for off, n in tensors if n <= short]
+    tasks.sort(key=lambda t: t[2] - t[3])   # longest first
     schedules = {}   # phases of a short tensor, by length (layer sizes repeat)
 
     def one(task):
         off, n, a, b = task
-        if n <= 8192:
-            # a short tensor whole, by the step simulator (the fold's P x P tiny reads cost more)
+        if n <= short:
             if n not in schedules:
                 schedules[n] = O.schedule(dims, n, 4)
             V = [I.fill_host(n, seed, r, dist, first=off) for r in range(P)]
@@ -888,7 +994,11 @@ def run_config(dev, cfg, fused=True, per_tensor=False):
     P, dims, count, dist, seed = cfg["P"], cfg["dims"], cfg["count"], cfg["dist"], cfg["seed"]
     say(f"config {cfg['name']}: P={P} dims={dims} count={count} dist={dist} seed={seed}")
     plan = D.ddl_ring_plan(dims, P, count)
+    D.ddl_plan_set_walk(plan, D.DDL_WALK_OFF)
     results = {"ddl_allreduce_sim": device_result(dev, cfg, D.ddl_allreduce_sim, plan)}
+    walk_plan = D.ddl_ring_plan(dims, P, count)
+    D.ddl_plan_set_walk(walk_plan, D.DDL_WALK_ON)
+    results["ddl_allreduce_sim, ring walk"] = device_result(dev, cfg, D.ddl_allreduce_sim, walk_plan)
     if fused:
         results["ddl_allreduce_fused_sim"] = device_result(dev, cfg, D.ddl_allreduce_fused_sim, plan)
     assert compare_whole(results, dims, seed, dist, [(0, count)], cfg["name"]) == count

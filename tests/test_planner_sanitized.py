@@ -59,6 +59,32 @@ static void one(const std::vector<int>& dims, uint64_t count, ddl_dtype_t dtype,
     } else if (!plan.whole.empty() || !plan.ragged.empty()) {
         std::abort();
     }
+    // ring-walk rows: in bounds, d distinct members of one ring, same range as the phases
+    ddl::build_walk(&plan);
+    if (off.size() == 1) {
+        size_t expect = 0;
+        for (int d : dims) expect += d > 1;
+        if (plan.walk_levels.size() != expect) std::abort();
+        uint64_t bytes = 0;
+        for (const ddl::WalkLevel& lv : plan.walk_levels) {
+            for (int half = 0; half < 2; ++half)
+                for (int r = 0; r < P; ++r) {
+                    const uint64_t* row = plan.walk_plan.data() + (half ? lv.gather_plan : lv.reduce_plan) + size_t(r) * (lv.d + 2);
+                    if (row[0] + row[1] > count || row[1] > lv.max_n || row[2] != (uint64_t)r) std::abort();
+                    for (int i = 0; i < lv.d; ++i) {
+                        if (row[2 + i] >= (uint64_t)P) std::abort();
+                        for (int j = 0; j < i; ++j)
+                            if (row[2 + i] == row[2 + j]) std::abort();
+                    }
+                    const bool last = &lv == &plan.walk_levels.back();
+                    bytes += row[1] * plan.elem_size * (last ? (half ? 0 : 2 * lv.d) : (half ? lv.d : 2 * lv.d - 1));
+                }
+        }
+        if (bytes != plan.walk_bytes || plan.walk_bytes > plan.bytes_total) std::abort();
+        if (plan.walk_words * 8 > (64u << 20)) std::abort();
+    } else if (!plan.walk_levels.empty()) {
+        std::abort();
+    }
     int levels = 0;
     for (int d : dims) levels += d > 1;
     if (P <= 64 && levels >= 1) {
