@@ -39,7 +39,7 @@ extern "C" {
 typedef struct ddl_plan ddl_plan_t;
 
 /* Element types.  Sums are formed in the element type itself, one rounding per addition,
- * round-to-nearest-even (the paper speaks of "floating point entries" of 4 bytes: 90 M
+ * round-to-nearest-even (Sec. 4.3 sizes the gradient vector at 4 bytes per element: 90 M
  * entries = 350 MB).  For the 16-bit types that is the correctly rounded 16-bit sum (bf16
  * is widened to binary32, added there and rounded once, which gives the same value). */
 typedef enum {
@@ -83,8 +83,8 @@ ddl_plan_t* ddl_ring_plan(const int* dims, int m, int P, size_t count, ddl_dtype
 
 /*
  * The same for a buffer that holds several tensors, each reduced on its own (a network's
- * gradients are a list of per-layer tensors; Sec. 4.1: an object wraps "a tensor of
- * gradients").  Tensor s occupies elements [tensor_off[s], tensor_off[s] + tensor_count[s])
+ * gradients are a list of per-layer tensors; Sec. 4.1: the objects the library works on are
+ * such tensors plus metadata).  Tensor s occupies elements [tensor_off[s], tensor_off[s] + tensor_count[s])
  * of every learner's buffer of `count` elements; tensors must be given in ascending order,
  * must not overlap, and must start on 16-byte granules (DDL_ERR_ALIGN otherwise).  Every
  * tensor is chunked by itself (tiny tensors give empty chunks), but all transfers of one
@@ -222,7 +222,7 @@ ddl_status_t ddl_allreduce_sim_timed(void** bufs, int P, const ddl_plan_t* plan,
                                      float* gather_ms);
 
 /*
- * Assignment (Sec. 4.1: "the most basic operation", object A receives a copy of object B):
+ * Assignment (Sec. 4.1: the elementary operation of the library, one object receives a copy of another):
  * dst[0 .. count) <- src[0 .. count), both DEVICE pointers, 16-byte aligned, not
  * overlapping, with the copy kernel of the all-gather phases.  Needs no plan.  Enqueued on
  * `stream`, does not synchronise.  DDL_ERR_ARG for NULL or overlapping ranges (count > 0),

@@ -8,7 +8,7 @@ smoke check and the benchmark's CPU-baseline leg may import this module.
 What the paper fixes (Sec. 4.3, "Topology aware communication"):
   * the result: R = sum_{j=1..N} V_j, delivered to every learner;
   * a ring over N nodes reduces in N-1 phases, each phase being N concurrent
-    transfers of 1/N of the data, and the result then has to be copied to all
+    transfers of an N-th of the data each, and the result then has to be copied to all
     learners with the same amount of traffic;
   * the multi-dimensional variant places the N learners in an m-dimensional box
     with N = d_1 * d_2 * ... * d_m, dimension 1 riding the fastest links;
@@ -54,7 +54,7 @@ import numpy as np
 
 
 # --------------------------------------------------------------------------------------
-# Box geometry (Sec. 4.3: "m-dimensional box", N = d_1 * ... * d_m)
+# Box geometry (Sec. 4.3: the learners form a box of m dimensions, N = d_1 * ... * d_m)
 # --------------------------------------------------------------------------------------
 def coords(r: int, dims) -> tuple:
     """Box coordinates (c_1..c_m) of learner rank r; c_1 varies fastest.
@@ -85,7 +85,7 @@ def neighbour(r: int, dims, t: int) -> int:
 
 
 # --------------------------------------------------------------------------------------
-# Chunking ("each transfer carries 1/N of the data", Sec. 4.3; uneven sizes: a reading)
+# Chunking (Sec. 4.3: every transfer of a phase carries an N-th of the data; uneven sizes: a reading)
 # --------------------------------------------------------------------------------------
 def granule(dtype) -> int:
     """Elements per 16-byte granule; chunk boundaries fall on granule multiples."""
@@ -310,7 +310,7 @@ def bf16_add(x: np.ndarray, y: np.ndarray) -> np.ndarray:
 
 # --------------------------------------------------------------------------------------
 # Several tensors per learner, each reduced on its own (the gradients of a network are a
-# list of per-layer tensors, Sec. 4.1: a DDL object wraps "a tensor of gradients")
+# list of per-layer tensors; Sec. 4.1: the library's objects are such tensors plus metadata)
 # --------------------------------------------------------------------------------------
 def schedule_tensors(dims, segments, G: int) -> list:
     """Phases when every tensor (off, n) of `segments` is chunked and reduced by itself but

@@ -1,5 +1,5 @@
 // gfx950 kernels of the simulated multi-ring allreduce: one launch executes all P transfers
-// of one phase (Sec. 4.3: a phase is N concurrent transfers of 1/N of the data).
+// of one phase (Sec. 4.3: a phase is N concurrent transfers of an N-th of the data each).
 //
 //   reduce_add_step : dst[off .. off+n) <- dst[..] + src[..]   (Sec. 4.1 ReduceScatter phase)
 //   copy_step       : dst[off .. off+n) <- src[..]             (Sec. 4.1 AllGather phase,
