@@ -32,6 +32,12 @@ HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 # copy of known size).  Recorded figures, not measured by this program: a counter run needs
 # the profiler around the process.  The summaries that hold them are named beside them.
 RECORDED_TRAFFIC = {
+    "c5_box4x8x8_resnet101_22k": {
+        "bytes_per_launch": 15705330190,
+        "source": "profiles/all_kernels_c5_box4x8x8_resnet101_22k_hbm_traffic.txt: rocprofv3 --pmc FETCH_SIZE and "
+                  "WRITE_SIZE runs of this program, average over reduce_add_step's 17 launches per allreduce "
+                  "(algorithmic 15705426420); recorded there, not measured in this run",
+    },
 }
 
 
@@ -213,17 +219,19 @@ def box_sweep(torch, D, dev, P=256, iters=30, counts=(4096, 65536, 1 << 20), box
         for dims in boxes:
             plan = D.ddl_ring_plan(dims, P, count)
             D.ddl_plan_prepare(plan)
-            D.ddl_plan_set_walk(plan, D.DDL_WALK_OFF)
-            for _ in range(3):
-                D.ddl_allreduce_sim(ptrs, P, plan, count, D.DDL_F32, stream)
-            torch.cuda.synchronize()
-            t0 = time.perf_counter()
-            for _ in range(iters):
-                D.ddl_allreduce_sim(ptrs, P, plan, count, D.DDL_F32, stream)
-            torch.cuda.synchronize()
-            us = (time.perf_counter() - t0) / iters * 1e6
-            rows.append({"count": count, "dims": dims, "phases": D.ddl_plan_num_steps(plan),
-                         "bytes": D.ddl_plan_bytes_moved(plan), "us": round(us, 1)})
+            us = {}
+            for mode, key in ((D.DDL_WALK_OFF, "us"), (D.DDL_WALK_ON, "us_ring_walk")):
+                D.ddl_plan_set_walk(plan, mode)
+                for _ in range(3):
+                    D.ddl_allreduce_sim(ptrs, P, plan, count, D.DDL_F32, stream)
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                for _ in range(iters):
+                    D.ddl_allreduce_sim(ptrs, P, plan, count, D.DDL_F32, stream)
+                torch.cuda.synchronize()
+                us[key] = round((time.perf_counter() - t0) / iters * 1e6, 1)
+            rows.append(dict(count=count, dims=dims, phases=D.ddl_plan_num_steps(plan),
+                             bytes=D.ddl_plan_bytes_moved(plan), **us))
         del bufs, ptrs
     A = np.array([[r["phases"], r["bytes"]] for r in rows], dtype=np.float64)
     y = np.array([r["us"] * 1e-6 for r in rows])
