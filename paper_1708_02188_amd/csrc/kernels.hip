@@ -659,8 +659,21 @@ __global__ __launch_bounds__(256) void resolve_walk(const PtrTable table, void* 
 }
 
 #ifndef DDL_WALK_ROWS
-#define DDL_WALK_ROWS 2
+#define DDL_WALK_ROWS 4
 #endif
+#ifndef DDL_WALK_GATHER_ROWS
+#define DDL_WALK_GATHER_ROWS 1
+#endif
+#ifndef DDL_WALK_GATHER_NT
+#define DDL_WALK_GATHER_NT 0
+#endif
+template <typename V> __device__ __forceinline__ void walk_gather_store(DDL_GLOBAL V* p, V v) {
+#if DDL_WALK_GATHER_NT
+    __builtin_nontemporal_store(v, p);
+#else
+    *p = v;
+#endif
+}
 constexpr int kWalkBatch = 8;   // ring positions whose rows a wave loads before it adds and stores
 
 // What a walk does at every place of a chunk.  WALK_BOTH serves the last dimension of a whole
@@ -685,7 +698,7 @@ __global__ __launch_bounds__(64) void walk_kernel(const uint64_t* table_, int d,
     typedef typename Elem<T>::V V;
     typedef typename Elem<T>::S S;
     constexpr int64_t VL = 16 / sizeof(S);
-    constexpr int R = MODE == WALK_GATHER ? 1 : DDL_WALK_ROWS;
+    constexpr int R = MODE == WALK_GATHER ? DDL_WALK_GATHER_ROWS : DDL_WALK_ROWS;
     constexpr int64_t kTileVecs = int64_t(R) * 64;
     const DDL_CONST uint64_t* row = (const DDL_CONST uint64_t*)table_ + size_t(blockIdx.y) * (d + 1);
     const int64_t n = int64_t(row[0]);
@@ -726,7 +739,7 @@ __global__ __launch_bounds__(64) void walk_kernel(const uint64_t* table_, int d,
             if (MODE != WALK_REDUCE) {
                 for (int i = MODE == WALK_BOTH ? 0 : 1; i < d; ++i) {
 #pragma unroll
-                    for (int r = 0; r < R; ++r) gather_store((DDL_GLOBAL V*)(addr[i] + byte_off) + r * 64, acc[r]);
+                    for (int r = 0; r < R; ++r) walk_gather_store((DDL_GLOBAL V*)(addr[i] + byte_off) + r * 64, acc[r]);
                 }
             }
         } else {
@@ -748,7 +761,7 @@ template <typename T>
 hipError_t launch_walk_typed(const ddl_plan& plan, const WalkLevel& level, const uint64_t* d_rows, int mode,
                              hipStream_t stream) {
     constexpr uint64_t VL = 16 / sizeof(typename Elem<T>::S);
-    const uint64_t tile_vecs = uint64_t(mode == WALK_GATHER ? 1 : DDL_WALK_ROWS) * 64;
+    const uint64_t tile_vecs = uint64_t(mode == WALK_GATHER ? DDL_WALK_GATHER_ROWS : DDL_WALK_ROWS) * 64;
     uint64_t tiles = (level.max_n / VL + 1 + (kRowVecs - 1) + tile_vecs - 1) / tile_vecs;
     const uint64_t max_x = (DDL_MAX_GRID_THREADS / 64 - 1) / uint64_t(plan.P);
     if (tiles > max_x) tiles = max_x;
