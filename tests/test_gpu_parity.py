@@ -425,6 +425,43 @@ def test_one_plan_two_streams_disjoint_buffer_sets(dev):
         assert_bitwise(B[j].cpu().numpy(), fold_b, f"fused stream b learner={j}")
 
 
+def test_one_plan_from_four_host_threads(dev):
+    """Four host threads, each with its own stream and buffer set, call through one plan at
+    the same time (the binding releases the GIL inside the library): slots are found, created
+    and bound under the plan's lock; every thread's result is its own oracle result."""
+    import threading
+    dims, P, count, rounds = [2, 4], 8, 70001, 6
+    plan = D.ddl_ring_plan(dims, P, count)
+    rng = np.random.default_rng(5150)
+    Vs = [[rng.uniform(-1, 1, count).astype(np.float32) * 1e-2 for _ in range(P)] for _ in range(4)]
+    sets = [upload(V, dev) for V in Vs]
+    streams = [torch.cuda.Stream() for _ in range(4)]
+    torch.cuda.synchronize()
+    errors = []
+
+    def work(k):
+        try:
+            for i in range(rounds):
+                entry = D.ddl_allreduce_fused_sim if i % 3 == 2 else D.ddl_allreduce_sim
+                entry(sets[k], P, plan, count, D.DDL_F32, streams[k])
+            streams[k].synchronize()
+        except Exception as e:   # surfaced below: an exception in a thread would otherwise be lost
+            errors.append(repr(e))
+
+    threads = [threading.Thread(target=work, args=(k,)) for k in range(4)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not errors, errors
+    for k in range(4):
+        want = Vs[k]
+        for _ in range(rounds):
+            want = O.allreduce_steps(want, dims)
+        for j, g in enumerate(download(sets[k])):
+            assert_bitwise(g, want[j], f"thread {k} learner={j}")
+
+
 def test_more_buffer_sets_than_binding_slots(dev):
     """Slots are rebound, least recently used first, once the plan holds its maximum."""
     dims, P, count = [2, 2], 4, 5003
