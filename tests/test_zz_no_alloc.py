@@ -49,6 +49,39 @@ def test_noalloc_entry_equals_allocating_entry_twice_in_a_row():
     both_entries(dev, [2], 5, 4)
 
 
+def test_noalloc_entry_under_stream_capture():
+    """Its reason to exist: captured into a HIP graph (nothing may allocate there), replayed
+    with eager calls of both entry points in between; every replay gives the oracle's bits."""
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a device")
+    dev = torch.device("cuda:0")
+    dims, P, count = [4, 2, 2], 16, 50021
+    rng = np.random.default_rng(77)
+    V = [rng.uniform(-1, 1, count).astype(np.float32) for _ in range(P)]
+    want = O.allreduce_steps(V, dims)
+    plan = D.ddl_ring_plan(dims, P, count)
+    D.ddl_plan_prepare(plan)   # set-up: looks the static array's address up on this device
+    bufs = [torch.from_numpy(v).to(dev) for v in V]
+    other = [torch.ones(count, dtype=torch.float32, device=dev) for _ in range(P)]
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    torch.cuda.synchronize()
+    say("  capturing ddl_allreduce_sim_noalloc")
+    with torch.cuda.graph(graph, stream=side):
+        D.ddl_allreduce_sim_noalloc(bufs, P, plan, count, D.DDL_F32, torch.cuda.current_stream())
+    for replay in range(3):
+        # eager calls in between rewrite the shared static array for other buffers
+        D.ddl_allreduce_sim_noalloc(other, P, plan, count)
+        D.ddl_allreduce_sim(other, P, plan, count)
+        for b, v in zip(bufs, V):
+            b.copy_(torch.from_numpy(v))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for j in range(P):
+            assert bufs[j].cpu().numpy().tobytes() == want[j].tobytes(), f"replay {replay}: learner {j} differs"
+
+
 def test_noalloc_entry_limits_are_errors():
     if not torch.cuda.is_available():
         pytest.fail("GPU tests need a device")
