@@ -203,6 +203,35 @@ def secondary(torch, D, I, dev, cfg, K, W, budget_bytes):
     return out
 
 
+def other_dtypes(torch, D, dev, cfg, K, W):
+    """The same kernels through the other element traits (16-, 32- and 64-bit), at one
+    configuration's shape; values are drawn by torch before every step, outside the events."""
+    P, dims, count = cfg["P"], cfg["dims"], cfg["count"]
+    stream = torch.cuda.current_stream()
+    out = []
+    for name, ddl, tdt in (("f64", D.DDL_F64, torch.float64), ("f16", D.DDL_F16, torch.float16),
+                           ("bf16", D.DDL_BF16, torch.bfloat16), ("i32", D.DDL_I32, torch.int32)):
+        bufs = [torch.empty(count, dtype=tdt, device=dev) for _ in range(P)]
+        ptrs = D.pointer_array(bufs)
+        plan = D.ddl_ring_plan(dims, P, count, ddl)
+        D.ddl_plan_prepare(plan)
+        D.ddl_plan_set_walk(plan, D.DDL_WALK_OFF)
+
+        def refill(i):
+            for b in bufs:
+                b.random_(-100, 100) if tdt == torch.int32 else b.normal_(0.0, 0.01)
+
+        ms, _ = time_calls(torch, stream, lambda i: D.ddl_allreduce_sim(ptrs, P, plan, count, ddl, stream), refill, K, W)
+        med = statistics.median(ms)
+        nbytes = D.ddl_plan_bytes_moved(plan)
+        gbs, frac = rate(nbytes, med)
+        out.append({"dtype": name, "ms_per_step": med, "bytes": nbytes, "achieved_GBs": gbs, "frac": frac,
+                    "GBs_per_virtual_learner": count * bufs[0].element_size() / (med * 1e-3) / 1e9})
+        del bufs, ptrs, plan
+        torch.cuda.empty_cache()
+    return {"workload": cfg["name"], "entry": "ddl_allreduce_sim, phase by phase", "results": out}
+
+
 def box_sweep(torch, D, dev, P=256, iters=30, counts=(4096, 65536, 1 << 20), boxes=None):
     """Sec. 4.3: a ring's time has a latency term per phase, so for many learners a box with
     fewer phases wins although it moves the same bytes.  On one GPU the latency of a phase
@@ -429,9 +458,10 @@ def main():
         torch.cuda.synchronize()
         del a, b
 
-    others, fit = None, None
+    others, fit, dtypes = None, None, None
     if not args.no_others:
         others = [secondary(torch, D, I, dev, c, K, W, budget) for c in I.CONFIGS if c["name"] != cfg["name"]]
+        dtypes = other_dtypes(torch, D, dev, I.CONFIGS[1], K, W)
         sweep = box_sweep(torch, D, dev, P=256, iters=20, counts=(4096, 262144),
                           boxes=[[256], [16, 16], [4, 8, 8], [2] * 8])
         fit = {"latency_per_phase_us": sweep["fit"]["latency_per_phase_us"],
@@ -463,6 +493,7 @@ def main():
         "fused_variant": fused,
         "per_tensor_variant": per_tensor,
         "other_configs": others,
+        "other_dtypes": dtypes,
         "latency_fit": fit,
         "cpu_baseline": cpu,
     }
