@@ -266,6 +266,17 @@ ddl_status_t ddl_allgather_fused_sim(void** bufs, int P, const ddl_plan_t* plan,
 
 /* ---- plan introspection (host only) ------------------------------------------------ */
 
+/*
+ * Self-check of a plan's schedule on the host (no GPU): every operation lies inside its
+ * tensor on 16-byte granules; in every phase each learner sends one operation and receives
+ * one, from its ring neighbour of that phase's dimension (Sec. 4.3: N concurrent transfers
+ * per phase); the range a learner receives never overlaps the range it sends in the same
+ * phase, so the transfers of a phase are free of races whatever their order; the learners'
+ * finest chunks tile every tensor; ring-walk rows follow their rings.  DDL_OK, or
+ * DDL_ERR_ARG for a NULL or inconsistent plan.  Cost: O(phases x tensors x P).
+ */
+ddl_status_t ddl_plan_verify(const ddl_plan_t* plan);
+
 /* 2 * sum_t (d_t - 1): Sec. 4.3, d-1 phases per ring, once reducing and once gathering.
  * Returns -1 for a NULL plan. */
 int ddl_plan_num_steps(const ddl_plan_t* plan);

@@ -19,7 +19,7 @@ _BINDING_NAMES = (
     "ddl_assign_sim", "ddl_allreduce_sim", "ddl_allreduce_sim_noalloc", "ddl_reduce_scatter_sim", "ddl_allgather_sim",
     "ddl_allreduce_sim_profile", "ddl_allreduce_sim_timed", "ddl_allreduce_fused_sim", "ddl_reduce_scatter_fused_sim", "ddl_allgather_fused_sim",
     "ddl_plan_fused_bytes",
-    "ddl_plan_num_steps", "ddl_plan_num_learners", "ddl_plan_bytes_moved", "ddl_plan_step_bytes",
+    "ddl_plan_verify", "ddl_plan_num_steps", "ddl_plan_num_learners", "ddl_plan_bytes_moved", "ddl_plan_step_bytes",
     "ddl_plan_get_step", "ddl_plan_owned_chunk", "ddl_plan_model_time", "ddl_choose_dims", "ddl_device_memory_info", "ddl_status_string",
     "library_path", "pointer_array",
 )

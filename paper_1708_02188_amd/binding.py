@@ -61,6 +61,7 @@ def _load():
         "ddl_allreduce_sim_profile": (i, sim_args + [ctypes.POINTER(ctypes.c_float)]),
         "ddl_allreduce_sim_timed": (i, sim_args + [ctypes.POINTER(ctypes.c_float),
                                                    ctypes.POINTER(ctypes.c_float)]),
+        "ddl_plan_verify": (i, [vp]),
         "ddl_plan_num_steps": (i, [vp]),
         "ddl_plan_num_learners": (i, [vp]),
         "ddl_plan_bytes_moved": (sz, [vp]),
@@ -255,6 +256,10 @@ def ddl_allreduce_sim_timed(bufs, P, plan, count, dtype=DDL_F32, stream=None):
     _check(_lib.ddl_allreduce_sim_timed(_ptr_array(bufs), P, _h(plan), count, dtype, _stream(stream),
                                         ctypes.byref(r), ctypes.byref(g)), "ddl_allreduce_sim_timed")
     return r.value, g.value
+
+
+def ddl_plan_verify(plan):
+    _check(_lib.ddl_plan_verify(_h(plan)), "ddl_plan_verify")
 
 
 def ddl_plan_num_steps(plan):

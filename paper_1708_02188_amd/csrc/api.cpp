@@ -591,6 +591,10 @@ ddl_status_t ddl_allreduce_sim_timed(void** bufs, int P, const ddl_plan_t* plan,
     return st;
 }
 
+ddl_status_t ddl_plan_verify(const ddl_plan_t* plan) {
+    return plan ? ddl::verify_plan(*plan) : DDL_ERR_ARG;
+}
+
 int ddl_plan_num_steps(const ddl_plan_t* plan) {
     return plan ? static_cast<int>(plan->steps.size()) : -1;
 }

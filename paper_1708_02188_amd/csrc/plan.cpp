@@ -3,6 +3,9 @@
 // reduce-scatter taking dimensions 1..m and the all-gather m..1 (Sec. 4.1 operations).
 #include "plan.h"
 
+#include <algorithm>
+#include <utility>
+
 namespace ddl {
 
 int dtype_size(ddl_dtype_t dtype) {
@@ -125,6 +128,71 @@ void build_schedule(ddl_plan* plan) {
     plan->first_gather = static_cast<int>(plan->steps.size());
     for (int t = m - 1; t >= 0; --t)
         for (int phase = 0; phase + 1 < plan->dims[t]; ++phase) emit(DDL_STEP_GATHER, t, phase);
+}
+
+ddl_status_t verify_plan(const ddl_plan& plan) {
+    const int P = plan.P;
+    const size_t S = plan.seg_off.size();
+    const uint64_t G = 16 / uint64_t(plan.elem_size);
+    const size_t per_step = S * size_t(P);
+    if (plan.ops.size() != plan.steps.size() * per_step) return DDL_ERR_ARG;
+    std::vector<int> stride(plan.dims.size() + 1, 1);
+    for (size_t t = 0; t < plan.dims.size(); ++t) stride[t + 1] = stride[t] * plan.dims[t];
+    std::vector<int> received(P);
+    for (size_t s = 0; s < plan.steps.size(); ++s) {
+        const Step& st = plan.steps[s];
+        if (st.dim < 0 || st.dim >= int(plan.dims.size())) return DDL_ERR_ARG;
+        const int d = plan.dims[st.dim];
+        for (size_t seg = 0; seg < S; ++seg) {
+            const Op* ops = plan.ops.data() + s * per_step + seg * P;
+            std::fill(received.begin(), received.end(), -1);
+            for (int r = 0; r < P; ++r) {
+                const Op& op = ops[r];
+                if (op.src != r || op.dst < 0 || op.dst >= P || received[op.dst] != -1) return DDL_ERR_ARG;
+                received[op.dst] = r;
+                // the receiver is the next position on the sender's ring of this dimension
+                const int pos = (r / stride[st.dim]) % d;
+                if (op.dst != r + ((pos + 1) % d - pos) * stride[st.dim]) return DDL_ERR_ARG;
+                if (op.off < plan.seg_off[seg] || op.off + op.n > plan.seg_off[seg] + plan.seg_count[seg])
+                    return DDL_ERR_ARG;
+                if (op.n > 0 && (op.off - plan.seg_off[seg]) % G != 0) return DDL_ERR_ARG;
+            }
+            for (int r = 0; r < P; ++r) {
+                // what learner r receives must not touch what it sends
+                const Op& out = ops[r];
+                const Op& in = ops[received[r]];
+                if (in.n > 0 && out.n > 0 && in.off < out.off + out.n && out.off < in.off + in.n) return DDL_ERR_ARG;
+            }
+        }
+    }
+    // finest chunks: along every ring of the last dimension... simply: all P chunks of a tensor,
+    // sorted by offset, tile it
+    for (size_t seg = 0; seg < S; ++seg) {
+        std::vector<std::pair<uint64_t, uint64_t>> chunks;
+        for (int r = 0; r < P; ++r)
+            chunks.emplace_back(plan.own_off[seg * P + r], plan.own_n[seg * P + r]);
+        std::sort(chunks.begin(), chunks.end());
+        uint64_t at = plan.seg_off[seg];
+        for (const auto& c : chunks) {
+            if (c.second == 0) continue;
+            if (c.first != at) return DDL_ERR_ARG;
+            at += c.second;
+        }
+        if (at != plan.seg_off[seg] + plan.seg_count[seg]) return DDL_ERR_ARG;
+    }
+    for (const WalkLevel& lv : plan.walk_levels)
+        for (int half = 0; half < 2; ++half)
+            for (int r = 0; r < P; ++r) {
+                const uint64_t* row = plan.walk_plan.data() + (half ? lv.gather_plan : lv.reduce_plan) +
+                                      size_t(r) * (size_t(lv.d) + 2);
+                if (row[0] + row[1] > plan.count || row[2] != uint64_t(r)) return DDL_ERR_ARG;
+                for (int i = 0; i + 1 < lv.d; ++i) {
+                    const int a = int(row[2 + i]);
+                    const int pos = (a / stride[lv.dim]) % lv.d;
+                    if (int(row[3 + i]) != a + ((pos + 1) % lv.d - pos) * stride[lv.dim]) return DDL_ERR_ARG;
+                }
+            }
+    return DDL_OK;
 }
 
 void build_walk(ddl_plan* plan) {

@@ -163,6 +163,15 @@ void build_walk(ddl_plan* plan);
 
 ddl_status_t validate_dims(const int* dims, int m, int P);
 
+// Self-check of a built plan (the schedule's race-freedom and coverage, independent of how
+// build_schedule derived it): every operation inside its tensor and on 16-byte granules; in
+// every phase each learner sends exactly one and receives exactly one operation per tensor,
+// along its ring of the phase's dimension; the range a learner receives is disjoint from the
+// range it sends in the same phase (so the P transfers of a phase can run in any order or
+// at once); each learner's finest chunks tile every tensor; the ring-walk rows list each
+// chunk's ring in order.  Returns DDL_OK or DDL_ERR_ARG.
+ddl_status_t verify_plan(const ddl_plan& plan);
+
 // Summation order of the step-fused allreduce; returns the number of box dimensions of
 // size > 1 ("levels") and the padded row length.  seq: P * padded, ctl: padded.
 int build_fused_order(const ddl_plan& plan, std::vector<uint32_t>* seq, std::vector<uint32_t>* ctl,

@@ -70,6 +70,17 @@ def test_plan_tables_equal_oracle_schedule(dims, count, dtype, itemsize):
     D.ddl_plan_free(plan)  # second free of the wrapper is a no-op
 
 
+@pytest.mark.parametrize("dims,count", PLAN_CASES)
+def test_plan_self_check_accepts_every_plan(dims, count):
+    P = prod(dims)
+    D.ddl_plan_verify(D.ddl_ring_plan(dims, P, count))
+    D.ddl_plan_verify(D.ddl_ring_plan(dims, P, count, D.DDL_F16))
+    if count >= 64:
+        D.ddl_plan_verify(D.ddl_ring_plan_tensors(dims, P, [0, 16, 48], [9, 32, count - 48], count))
+    with pytest.raises(D.DdlError):
+        D.ddl_plan_verify(None)
+
+
 def test_bytes_closed_form_at_the_benchmark_sizes():
     # 5 * sizeof * count * (P - 1) needs count divisible by G*P; otherwise within a granule per op
     for cfg in I.CONFIGS:

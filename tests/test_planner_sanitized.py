@@ -85,6 +85,30 @@ static void one(const std::vector<int>& dims, uint64_t count, ddl_dtype_t dtype,
     } else if (!plan.walk_levels.empty()) {
         std::abort();
     }
+    // the self-check accepts the plan and trips on planted mistakes
+    if (ddl::verify_plan(plan) != DDL_OK) std::abort();
+    if (!plan.ops.empty() && P > 1 && count >= 64 * (uint64_t)P) {
+        size_t first = 0;
+        while (plan.ops[first].n == 0) ++first;
+        const ddl::Op keep = plan.ops[first];
+        plan.ops[first].dst = keep.src;                          // a transfer to the wrong learner
+        if (ddl::verify_plan(plan) == DDL_OK) std::abort();
+        plan.ops[first] = keep;
+        plan.ops[first].off += 1;                                // off the granule grid
+        if (ddl::verify_plan(plan) == DDL_OK) std::abort();
+        plan.ops[first] = keep;
+        // a learner that receives the very range it sends in the first phase: a race
+        const int nb = plan.ops[0].dst;
+        const ddl::Op keep_nb = plan.ops[nb];
+        plan.ops[nb].off = plan.ops[0].off;
+        plan.ops[nb].n = plan.ops[0].n;
+        if (plan.ops[0].n > 0 && ddl::verify_plan(plan) == DDL_OK) std::abort();
+        plan.ops[nb] = keep_nb;
+        plan.own_n[0] += G;                                      // chunks no longer tile the tensor
+        if (ddl::verify_plan(plan) == DDL_OK) std::abort();
+        plan.own_n[0] -= G;
+        if (ddl::verify_plan(plan) != DDL_OK) std::abort();
+    }
     int levels = 0;
     for (int d : dims) levels += d > 1;
     if (P <= 64 && levels >= 1) {
