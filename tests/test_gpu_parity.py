@@ -758,12 +758,12 @@ def random_box(rng, max_P=48):
 def test_random_sweep_against_oracle(dev):
     rng = np.random.default_rng(20260101)
     dtypes = [D.DDL_F32, D.DDL_F64, D.DDL_I32, D.DDL_F16, D.DDL_BF16]
-    for case in range(60):
+    for case in range(100):
         dims = random_box(rng)
         P = prod(dims)
         dtype = dtypes[int(rng.integers(0, len(dtypes)))]
         count = int(rng.choice([0, 1, 3, 17, 255, 1024, 4097, 30011, 200003]) + rng.integers(0, 9))
-        entry = ["allreduce", "fused", "tensors"][int(rng.integers(0, 3))]
+        entry = ["allreduce", "fused", "tensors", "walk", "noalloc"][int(rng.integers(0, 5))]
         levels = sum(d > 1 for d in dims)
         if entry == "fused" and levels > 4:
             entry = "allreduce"
@@ -782,8 +782,11 @@ def test_random_sweep_against_oracle(dev):
                 want = O.allreduce_tensors(V, dims, segments, add=add)
             else:
                 plan = D.ddl_ring_plan(dims, P, count, dtype)
+                D.ddl_plan_set_walk(plan, D.DDL_WALK_ON if entry == "walk" else D.DDL_WALK_OFF)
                 if entry == "fused":
                     D.ddl_allreduce_fused_sim(bufs, P, plan, count, dtype)
+                elif entry == "noalloc":
+                    D.ddl_allreduce_sim_noalloc(bufs, P, plan, count, dtype)
                 else:
                     D.ddl_allreduce_sim(bufs, P, plan, count, dtype)
                 want = O.allreduce_steps(V, dims, add=add)
