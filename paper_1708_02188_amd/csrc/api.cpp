@@ -144,10 +144,18 @@ ddl::Binding* new_binding(const ddl_plan* plan, const DeviceTables* t, bool fuse
 ddl_status_t acquire_binding(void** bufs, int P, const ddl_plan* plan, hipStream_t stream, bool fused,
                              DeviceTables** tables_out, ddl::Binding** out, bool* was_bound) {
     std::lock_guard<std::mutex> lock(plan->mu);
-    DeviceTables* t = nullptr;
-    ddl_status_t st = device_tables_locked(plan, &t);
-    if (st != DDL_OK) return st;
     const bool capturing = stream_is_capturing(stream);
+    DeviceTables* t = nullptr;
+    if (capturing) {
+        // nothing may allocate or copy now: the tables must exist (ddl_plan_prepare)
+        int device = -1;
+        if (hipGetDevice(&device) != hipSuccess) return DDL_ERR_HIP;
+        for (DeviceTables* have : plan->tables)
+            if (have->device == device) t = have;
+        if (t == nullptr) return DDL_ERR_UNSUPPORTED;
+    }
+    ddl_status_t st = t ? DDL_OK : device_tables_locked(plan, &t);
+    if (st != DDL_OK) return st;
     if (fused && t->fused_seq == nullptr) {
         if (capturing) return DDL_ERR_UNSUPPORTED;  // ddl_plan_prepare was not called
         st = fused_tables_locked(plan, t);
