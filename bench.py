@@ -450,6 +450,22 @@ def main():
     n_sets = len(w.sets)
     w.close()
 
+    # context: a plain 1 GiB device-to-device copy by the HIP runtime (what torch's copy_ calls)
+    # and by ddl_assign_sim, the all-gather phase's kernel on one range
+    copies = None
+    if not args.no_others:
+        a = torch.zeros(2 ** 28, dtype=torch.float32, device=dev)
+        b = torch.empty_like(a)
+        stream = torch.cuda.current_stream()
+        ms_rt, _ = time_calls(torch, stream, lambda i: b.copy_(a), lambda i: None, 10, 2)
+        ms_as, _ = time_calls(torch, stream, lambda i: D.ddl_assign_sim(b, a, a.numel(), D.DDL_F32, stream),
+                              lambda i: None, 10, 2)
+        copies = {"bytes_read_plus_written": 2 ** 31,
+                  "hip_runtime_copy_GBs": 2 ** 31 / (statistics.median(ms_rt) * 1e-3) / 1e9,
+                  "ddl_assign_sim_GBs": 2 ** 31 / (statistics.median(ms_as) * 1e-3) / 1e9}
+        del a, b
+        torch.cuda.empty_cache()
+
     if args.calib_copy_mib > 0:
         a = torch.zeros(args.calib_copy_mib * 2 ** 18, dtype=torch.float32, device=dev)
         b = torch.empty_like(a)
@@ -494,6 +510,7 @@ def main():
         "per_tensor_variant": per_tensor,
         "other_configs": others,
         "other_dtypes": dtypes,
+        "plain_copy_1GiB": copies,
         "latency_fit": fit,
         "cpu_baseline": cpu,
     }
