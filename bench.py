@@ -232,6 +232,57 @@ def other_dtypes(torch, D, dev, cfg, K, W):
     return {"workload": cfg["name"], "entry": "ddl_allreduce_sim, phase by phase", "results": out}
 
 
+def overlap_with_compute(torch, D, I, dev, cfg, reps=10):
+    """Sec. 5 notes that the Torch integration does not overlap communication with compute.
+    Here: the gradient buffer cut into four buckets, each with its own plan, allreduced one
+    after the other on a side stream while a dense matrix product (torch's, a stand-in for
+    the backward pass of the next layers) runs on the main stream; against both alone."""
+    P, dims, count = cfg["P"], cfg["dims"], cfg["count"]
+    bufs = [torch.zeros(count, dtype=torch.float32, device=dev) for _ in range(P)]
+    cuts = [count * k // 4 // 4 * 4 for k in range(4)] + [count]
+    buckets = []
+    for a, b in zip(cuts, cuts[1:]):
+        plan = D.ddl_ring_plan(dims, P, b - a)
+        D.ddl_plan_prepare(plan)
+        D.ddl_plan_set_walk(plan, D.DDL_WALK_OFF)
+        buckets.append((plan, D.pointer_array([x[a:b] for x in bufs]), b - a))
+    n = 8192
+    x = torch.randn(n, n, dtype=torch.bfloat16, device=dev)
+    y = torch.randn(n, n, dtype=torch.bfloat16, device=dev)
+    main, side = torch.cuda.current_stream(), torch.cuda.Stream()
+
+    def allreduce(stream):
+        for plan, ptrs, nb in buckets:
+            D.ddl_allreduce_sim(ptrs, P, plan, nb, D.DDL_F32, stream)
+
+    def timed(comm, compute):
+        ms = []
+        for _ in range(reps + 2):
+            for b in bufs:
+                b.zero_()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(main)
+            if comm:
+                side.wait_event(e0)
+                allreduce(side)
+            if compute:
+                torch.matmul(x, y)
+            if comm:
+                done = torch.cuda.Event()
+                done.record(side)
+                main.wait_event(done)
+            e1.record(main)
+            torch.cuda.synchronize()
+            ms.append(e0.elapsed_time(e1))
+        return statistics.median(ms[2:])
+
+    t_comm, t_comp, t_both = timed(True, False), timed(False, True), timed(True, True)
+    return {"workload": cfg["name"], "buckets": 4, "compute": f"bf16 matmul {n}x{n}x{n} (torch)",
+            "allreduce_alone_ms": t_comm, "compute_alone_ms": t_comp, "both_ms": t_both,
+            "overlap": (t_comm + t_comp - t_both) / min(t_comm, t_comp)}
+
+
 def box_sweep(torch, D, dev, P=256, iters=30, counts=(4096, 65536, 1 << 20), boxes=None):
     """Sec. 4.3: a ring's time has a latency term per phase, so for many learners a box with
     fewer phases wins although it moves the same bytes.  On one GPU the latency of a phase
@@ -474,10 +525,11 @@ def main():
         torch.cuda.synchronize()
         del a, b
 
-    others, fit, dtypes = None, None, None
+    others, fit, dtypes, overlap = None, None, None, None
     if not args.no_others:
         others = [secondary(torch, D, I, dev, c, K, W, budget) for c in I.CONFIGS if c["name"] != cfg["name"]]
         dtypes = other_dtypes(torch, D, dev, I.CONFIGS[1], K, W)
+        overlap = overlap_with_compute(torch, D, I, dev, I.CONFIGS[1])
         sweep = box_sweep(torch, D, dev, P=256, iters=20, counts=(4096, 262144),
                           boxes=[[256], [16, 16], [4, 8, 8], [2] * 8])
         fit = {"latency_per_phase_us": sweep["fit"]["latency_per_phase_us"],
@@ -510,6 +562,7 @@ def main():
         "per_tensor_variant": per_tensor,
         "other_configs": others,
         "other_dtypes": dtypes,
+        "overlap_with_compute": overlap,
         "plain_copy_1GiB": copies,
         "latency_fit": fit,
         "cpu_baseline": cpu,
