@@ -71,6 +71,10 @@ enum { DDL_STEP_REDUCE = 0, DDL_STEP_GATHER = 1 };
 /* A plan stores phases x tensors x learners operations (56 bytes each, host + device);
  * plans beyond this many are refused with DDL_ERR_NOMEM. */
 #define DDL_MAX_PLAN_OPS (1ull << 26)
+/* A several-tensor plan also stores one work item per 16 KiB that the learners send (8 bytes
+ * on the host, 24 on the device per buffer set); plans of more than about this many items
+ * (count * sizeof(element) * (P - 1) / 8192) are refused with DDL_ERR_NOMEM. */
+#define DDL_MAX_LIST_ITEMS (1ull << 28)
 
 /*
  * Build the schedule for a box dims[0..m-1] (Sec. 4.3: N = d_1*...*d_m) over P learners

@@ -337,6 +337,10 @@ ddl_plan_t* make_plan(const int* dims, int m, int P, const size_t* seg_off, cons
         uint64_t phases = 0;
         for (int t = 0; t < m; ++t) phases += 2 * uint64_t(dims[t] - 1);
         if (phases * uint64_t(S) > DDL_MAX_PLAN_OPS / uint64_t(P)) st = DDL_ERR_NOMEM;
+        // several tensors: one work item per 16 KiB a learner sends, over both halves
+        if (S > 1 && P > 1 &&
+            count > DDL_MAX_LIST_ITEMS * uint64_t(8192) / (uint64_t(elem) * uint64_t(P - 1)))
+            st = DDL_ERR_NOMEM;
     }
     if (st != DDL_OK) {
         set_status(status, st);

@@ -325,6 +325,14 @@ def test_tensor_plan_tables_equal_oracle_schedule():
                 assert D.ddl_plan_owned_chunk_tensor(plan, s_i, O.rank_of(k, dims)) == (off + a, b - a)
 
 
+def test_tensor_plan_too_large_for_its_work_lists_is_refused():
+    # 2^38 fp32 elements over 64 learners would need 8e9 work items: refused before anything is built
+    count = 1 << 38
+    assert status_of(D.ddl_ring_plan_tensors, [4, 16], 64, [0, count // 2], [count // 2, count // 2], count) \
+        == D.DDL_ERR_NOMEM
+    D.ddl_plan_free(D.ddl_ring_plan([4, 16], 64, count))   # one tensor needs no lists
+
+
 def test_tensor_plan_argument_errors():
     ok = dict(dims=[2, 2], P=4, count=100)
     assert status_of(D.ddl_ring_plan_tensors, [2, 2], 4, [0, 10], [10, 10], 100) == D.DDL_ERR_ALIGN   # 10 % 4 != 0
