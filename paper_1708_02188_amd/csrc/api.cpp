@@ -451,6 +451,9 @@ ddl_status_t ddl_allreduce_sim(void** bufs, int P, const ddl_plan_t* plan, size_
 
 ddl_status_t ddl_allreduce_sim_noalloc(void** bufs, int P, const ddl_plan_t* plan, size_t count,
                                        ddl_dtype_t dtype, void* stream_v) {
+    // more learners than the kernel-argument table holds are refused before the argument
+    // check, which would need heap memory to sort that many pointers
+    if (plan != nullptr && bufs != nullptr && P > ddl::kKernargLearners) return DDL_ERR_UNSUPPORTED;
     ddl_status_t st = check_call(bufs, P, plan, count, dtype);
     if (st != DDL_OK) return st;
     const size_t steps = plan->steps.size();
