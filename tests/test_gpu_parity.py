@@ -740,6 +740,27 @@ def test_striding_and_split_launch_paths_in_a_small_grid_build(dev):
     assert run.returncode == 0 and "stride paths ok" in run.stdout, run.stderr[-3000:]
 
 
+def test_four_thousand_learners(dev):
+    """4096 learners as the box [16,16,16]: sixteen slices of the pointer table, rings of 16
+    (two load batches in the ring walk), chunks of a handful of elements."""
+    dims, P, count = [16, 16, 16], 4096, 20001
+    say(f"P={P} dims={dims} count={count}")
+    V = [I.fill_host(count, 9, j, "uniform") for j in range(P)]
+    want = O.allreduce_steps(V, dims)
+    for mode in (D.DDL_WALK_OFF, D.DDL_WALK_ON):
+        plan = D.ddl_ring_plan(dims, P, count)
+        D.ddl_plan_verify(plan)
+        D.ddl_plan_set_walk(plan, mode)
+        bufs = upload(V, dev)
+        D.ddl_allreduce_sim(bufs, P, plan, count)
+        torch.cuda.synchronize()
+        for j in range(P):
+            assert_bitwise(bufs[j].cpu().numpy(), want[j], f"walk mode {mode} learner={j}")
+    with pytest.raises(D.DdlError) as e:
+        D.ddl_allreduce_fused_sim(bufs, P, plan, count)
+    assert e.value.status == D.DDL_ERR_UNSUPPORTED
+
+
 # ---------------------------------------------------------------------------------------
 # seeded random sweep over boxes, lengths, element types and entry points
 # ---------------------------------------------------------------------------------------
