@@ -388,7 +388,8 @@ hipError_t launch_list_typed(const Step& step, int learners, const ResolvedOp* d
     // Measured on MI355X with ResNet-sized tensor lists: spreading the ragged items through
     // the launch gains 2-3 % with 16 and 64 learners and loses 15 % with 256, where the
     // ragged items of one phase touch small ranges of some five hundred different buffers
-    // (and so evict the address translations the streaming rows use); then they go last.
+    // (which presumably evicts the address translations the streaming rows use); then they
+    // go last.
 #ifndef DDL_LIST_INTERLEAVE_MAX_LEARNERS
 #define DDL_LIST_INTERLEAVE_MAX_LEARNERS 64
 #endif
