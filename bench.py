@@ -69,16 +69,13 @@ def rate(nbytes, ms):
 class Workload:
     """One configuration resident on the device: `n_sets` sets of P learner buffers."""
 
-    stagger_bytes = 0   # learner j's buffer starts (j % 4) * stagger_bytes into its allocation
-
     def __init__(self, torch, D, I, dev, cfg, n_sets):
         self.torch, self.D, self.I, self.cfg = torch, D, I, cfg
         self.P, self.dims, self.count = cfg["P"], cfg["dims"], cfg["count"]
         self.dist, self.seed = cfg["dist"], cfg["seed"]
         self.stream = torch.cuda.current_stream()
-        pad = self.stagger_bytes // 4
-        self.sets = [[torch.empty(self.count + 3 * pad, dtype=torch.float32, device=dev)[(j % 4) * pad:][:self.count]
-                      for j in range(self.P)] for _ in range(n_sets)]
+        self.sets = [[torch.empty(self.count, dtype=torch.float32, device=dev) for _ in range(self.P)]
+                     for _ in range(n_sets)]
         # pointer arrays are built once: the timed calls marshal nothing
         self.ptrs = [D.pointer_array(s) for s in self.sets]
         self.plan = D.ddl_ring_plan(self.dims, self.P, self.count)
@@ -384,8 +381,6 @@ def main():
     ap.add_argument("--seed", type=int, default=None, help="generator seed (default: the configuration's)")
     ap.add_argument("--dist", choices=["int8", "uniform", "normal"], default=None)
     ap.add_argument("--sets-gib", type=float, default=200.0, help="HBM budget for the input sets (two if they fit)")
-    ap.add_argument("--stagger-kib", type=int, default=0,
-                    help="start learner j's buffer (j mod 4) * this many KiB into its allocation")
     ap.add_argument("--profile-passes", type=int, default=10)
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
     ap.add_argument("--no-others", action="store_true", help="skip the secondary configurations and the box sweep")
@@ -435,7 +430,6 @@ def main():
             cfg["seed"] = args.seed
         if args.dist is not None:
             cfg["dist"] = args.dist
-    Workload.stagger_bytes = args.stagger_kib * 1024
     K, W = args.steps, args.warmup
     budget = int(args.sets_gib * 2 ** 30)
     resident = 4 * cfg["count"] * cfg["P"]
