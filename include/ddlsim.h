@@ -150,9 +150,8 @@ ddl_status_t ddl_plan_set_walk(const ddl_plan_t* plan, int mode);
  *          With count == 0 the pointers are not examined (empty buffers may be NULL).
  *   P, count, dtype must equal the plan's.
  * Enqueues one kernel per step (or per dimension, see ddl_plan_set_walk) on `stream` and
- * returns without synchronising; when the
- * stream has drained, every bufs[j] holds the sum, bit-identical across learners, formed in
- * the order the schedule fixes: within the ring of dimension t the partial sum of part k
+ * returns without synchronising; when the stream has drained, every bufs[j] holds the sum,
+ * bit-identical across learners, formed in the order the schedule fixes: within the ring of dimension t the partial sum of part k
  * starts at ring position k+1 and is extended by positions k+2, ..., k+d_t (= k).
  * Bindings: the kernels read absolute addresses from a per-plan table bound to one buffer
  * set ("binding slot").  A call whose P pointers equal those of an existing slot uses it as
@@ -165,8 +164,9 @@ ddl_status_t ddl_plan_set_walk(const ddl_plan_t* plan, int mode);
  * another stream still reads it, which the caller must then order.  Slots allocate device
  * memory when they are created; see ddl_plan_prepare for callers that must avoid that.
  * A call under stream capture records its own binding kernel into the caller's graph and
- * keeps its slot for the plan's lifetime (replays of that graph stay valid whatever runs in between);
- * if no slot is free and none can be created it returns DDL_ERR_UNSUPPORTED.
+ * keeps its slot for the plan's lifetime (replays of that graph stay valid whatever runs in
+ * between); if the plan's tables do not exist yet (ddl_plan_prepare), or no slot is free and
+ * none can be created, it returns DDL_ERR_UNSUPPORTED.
  * Errors are reported before anything is enqueued, except DDL_ERR_HIP for a failed launch.
  */
 ddl_status_t ddl_allreduce_sim(void** bufs, int P, const ddl_plan_t* plan, size_t count,
@@ -181,7 +181,7 @@ ddl_status_t ddl_allreduce_sim(void** bufs, int P, const ddl_plan_t* plan, size_
  * DDL_NOALLOC_MAX_OPS records (32 bytes each, 512 KiB, held by every GPU the library has
  * run on until the process ends) instead of the plan's device tables.  The only set-up is
  * the lookup of that array's address at the first call on a device (ddl_plan_prepare does
- * it too, so call that before a capture).
+ * it too, so call that before a capture).  Always runs phase by phase.
  * Limits, beyond which it returns DDL_ERR_UNSUPPORTED and enqueues nothing: P <= 256,
  * phases * P <= DDL_NOALLOC_MAX_OPS, plans of ddl_ring_plan only (one tensor).
  * All calls on one GPU share the array (each call rewrites the records it uses, nothing
