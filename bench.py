@@ -193,9 +193,14 @@ def secondary(torch, D, I, dev, cfg, K, W, budget_bytes):
     if "layers" in cfg["name"]:
         tplan, ntens = w.tensor_plan()
         if tplan is not None:
+            D.ddl_plan_set_walk(tplan, D.DDL_WALK_OFF)
             out["per_tensor_variant"] = w.measure(D.ddl_allreduce_sim, K, W, plan=tplan,
                                                   nbytes=D.ddl_plan_bytes_moved(tplan))
             out["per_tensor_variant"]["tensors"] = ntens
+            if D.ddl_plan_walk_bytes(tplan):
+                D.ddl_plan_set_walk(tplan, D.DDL_WALK_ON)
+                out["per_tensor_variant"]["ring_walk"] = w.measure(D.ddl_allreduce_sim, K, W, plan=tplan,
+                                                                   nbytes=D.ddl_plan_walk_bytes(tplan))
     w.close()
     return out
 
@@ -469,9 +474,14 @@ def main():
     per_tensor = None
     tplan, ntens = w.tensor_plan()
     if tplan is not None:
+        D.ddl_plan_set_walk(tplan, D.DDL_WALK_OFF)
         per_tensor = dict(entry="ddl_ring_plan_tensors + ddl_allreduce_sim", tensors=ntens,
                           **w.measure(D.ddl_allreduce_sim, K, W, plan=tplan, nbytes=D.ddl_plan_bytes_moved(tplan)))
         per_tensor["slowdown_vs_one_buffer"] = per_tensor["ms_per_step"] / ms_per_step
+        if D.ddl_plan_walk_bytes(tplan):
+            D.ddl_plan_set_walk(tplan, D.DDL_WALK_ON)
+            per_tensor["ring_walk"] = w.measure(D.ddl_allreduce_sim, K, W, plan=tplan,
+                                                nbytes=D.ddl_plan_walk_bytes(tplan))
         del tplan
 
     red, cpy = kernel_roofline(w, args.profile_passes) if args.profile_passes else (None, None)

@@ -135,7 +135,10 @@ ddl_status_t ddl_plan_reserve_bindings(const ddl_plan_t* plan, int slots);
  *                            (launch-bound: the saved phase boundaries dominate), else phases
  *   DDL_WALK_OFF             always phase by phase
  *   DDL_WALK_ON              always walk (DDL_ERR_UNSUPPORTED for a plan without the form:
- *                            several tensors, or rings too long for its tables)
+ *                            one whose walk tables, 2 * tensors * P * (d + 2) words summed over
+ *                            the dimensions, would exceed 2^24 words)
+ * Several-tensor plans walk too (every tensor's chunks round their rings, all of a
+ * dimension in one launch over a list of 4 KiB tiles).
  * The measurement entry points with an event per step always run phase by phase.
  */
 enum { DDL_WALK_AUTO = 0, DDL_WALK_OFF = 1, DDL_WALK_ON = 2 };

@@ -45,6 +45,7 @@ void release_tables(DeviceTables* t) {
     t->bindings.clear();
     release(&t->ops);
     release(&t->walk_plan);
+    release(&t->walk_items);
     release(&t->whole);
     release(&t->ragged);
     release(&t->fused_seq);
@@ -79,6 +80,7 @@ ddl_status_t device_tables_locked(const ddl_plan* plan, DeviceTables** out) {
     bool ok = true;
     if (!plan->ops.empty()) ok = upload(&t->ops, plan->ops);
     if (ok && !plan->walk_plan.empty()) ok = upload(&t->walk_plan, plan->walk_plan);
+    if (ok && !plan->walk_items.empty()) ok = upload(&t->walk_items, plan->walk_items);
     if (ok && !plan->whole.empty()) ok = upload(&t->whole, plan->whole);
     if (ok && !plan->ragged.empty()) ok = upload(&t->ragged, plan->ragged);
     if (!ok) {
@@ -269,18 +271,18 @@ bool wants_walk(const ddl_plan* plan) {
 }
 
 // The reduce-scatter and / or the all-gather as ring walks: one launch per box dimension.
-ddl_status_t launch_walks(const ddl_plan* plan, const ddl::Binding* slot, bool reduce, bool gather,
-                          hipStream_t stream) {
+ddl_status_t launch_walks(const ddl_plan* plan, const DeviceTables* t, const ddl::Binding* slot, bool reduce,
+                          bool gather, hipStream_t stream) {
     const int levels = static_cast<int>(plan->walk_levels.size());
     // a whole allreduce takes the last dimension's reduce-scatter and all-gather in one launch
     const int both = reduce && gather ? levels - 1 : -1;
     if (reduce)
         for (int l = 0; l < levels; ++l)
-            if (ddl::launch_walk(*plan, plan->walk_levels[l], slot->walk, l == both ? 2 : 1, stream) != hipSuccess)
+            if (ddl::launch_walk(*plan, plan->walk_levels[l], slot->walk, t->walk_items, l == both ? 2 : 1, stream) != hipSuccess)
                 return DDL_ERR_HIP;
     if (gather)
         for (int l = levels - 1; l >= 0; --l)
-            if (l != both && ddl::launch_walk(*plan, plan->walk_levels[l], slot->walk, 0, stream) != hipSuccess)
+            if (l != both && ddl::launch_walk(*plan, plan->walk_levels[l], slot->walk, t->walk_items, 0, stream) != hipSuccess)
                 return DDL_ERR_HIP;
     return DDL_OK;
 }
@@ -310,7 +312,7 @@ ddl_status_t run_steps(void** bufs, int P, const ddl_plan* plan, size_t count, d
         std::lock_guard<std::mutex> lock(plan->mu);
         walk = events == nullptr && halves && first < last && slot->walk != nullptr && wants_walk(plan);
     }
-    if (walk) return launch_walks(plan, slot, reduce, gather, stream);
+    if (walk) return launch_walks(plan, t, slot, reduce, gather, stream);
     return launch_steps(plan, t, slot, first, last, stream, events);
 }
 

@@ -115,11 +115,12 @@ hipError_t launch_assign(ddl_dtype_t dtype, void* dst, const void* src, uint64_t
 // plan's walk rows (d_walk_plan, learner indices) to the caller's buffers in d_rows;
 // launch_walk runs one dimension over bound rows: mode 0 = its all-gather, 1 = its
 // reduce-scatter, 2 = both at once (the sum stored to all d positions: the last dimension of a
-// whole allreduce, whose gather overwrites its own partial sums).
+// whole allreduce, whose gather overwrites its own partial sums).  d_items: the plan's tiles
+// (several-tensor plans, else unused).
 hipError_t launch_resolve_walk(const ddl_plan& plan, const uint64_t* d_walk_plan, uint64_t* d_rows,
                                const PtrTable& table, void* const* d_ptrs, hipStream_t stream);
-hipError_t launch_walk(const ddl_plan& plan, const WalkLevel& level, const uint64_t* d_rows, int mode,
-                       hipStream_t stream);
+hipError_t launch_walk(const ddl_plan& plan, const WalkLevel& level, const uint64_t* d_rows,
+                       const BlockDesc* d_items, int mode, hipStream_t stream);
 
 // Copy the P learner pointers of the host array `bufs` into the device array d_ptrs, through
 // kernel arguments (kKernargLearners per launch); `bufs` is not referenced after return.

@@ -694,11 +694,67 @@ __device__ __forceinline__ void walk_place(const DDL_CONST uint64_t* addr, int d
         for (int i = 0; i < d; ++i) *(DDL_GLOBAL X*)(addr[i] + byte_off) = acc;
 }
 
-template <typename T, int MODE>
-__global__ __launch_bounds__(64) void walk_kernel(const uint64_t* table_, int d, unsigned tile_stride) {
+// One tile (R rows of 64 lanes x 16 bytes, starting at vector index `tile` of the chunk's
+// row-aligned tiling, which may begin before the chunk or reach past its end).
+template <typename T, int MODE, int R>
+__device__ __forceinline__ void walk_tile(const DDL_CONST uint64_t* addr, int d, int64_t n, int64_t nv,
+                                          int64_t tile, int64_t lane) {
     typedef typename Elem<T>::V V;
     typedef typename Elem<T>::S S;
     constexpr int64_t VL = 16 / sizeof(S);
+    constexpr int64_t kTileVecs = int64_t(R) * 64;
+    if (tile >= 0 && tile + kTileVecs <= nv) {
+        const uint64_t byte_off = uint64_t(tile + lane) * 16;
+        V acc[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) acc[r] = stream_load((const DDL_GLOBAL V*)(addr[0] + byte_off) + r * 64);
+        if (MODE != WALK_GATHER) {
+            for (int i0 = 1; i0 < d; i0 += kWalkBatch) {
+                V x[kWalkBatch][R];
+#pragma unroll
+                for (int j = 0; j < kWalkBatch; ++j)
+                    if (i0 + j < d) {
+#pragma unroll
+                        for (int r = 0; r < R; ++r)
+                            x[j][r] = stream_load((const DDL_GLOBAL V*)(addr[i0 + j] + byte_off) + r * 64);
+                    }
+#pragma unroll
+                for (int j = 0; j < kWalkBatch; ++j)
+                    if (i0 + j < d) {
+#pragma unroll
+                        for (int r = 0; r < R; ++r) {
+                            acc[r] = Elem<T>::sum(x[j][r], acc[r]);
+                            if (MODE == WALK_REDUCE)
+                                stream_store((DDL_GLOBAL V*)(addr[i0 + j] + byte_off) + r * 64, acc[r]);
+                        }
+                    }
+            }
+        }
+        if (MODE != WALK_REDUCE) {
+            for (int i = MODE == WALK_BOTH ? 0 : 1; i < d; ++i) {
+#pragma unroll
+                for (int r = 0; r < R; ++r) walk_gather_store((DDL_GLOBAL V*)(addr[i] + byte_off) + r * 64, acc[r]);
+            }
+        }
+    } else {
+        // first or last rows of the chunk: per-lane bounds
+        for (int r = 0; r < R; ++r) {
+            const int64_t v = tile + r * 64 + lane;
+            if (v >= 0 && v < nv) {
+                walk_place<T, V, MODE>(addr, d, uint64_t(v) * 16);
+            } else if (v == nv) {
+                // the buffer's last, short vector: element by element
+                for (int64_t e = nv * VL; e < n; ++e) walk_place<T, S, MODE>(addr, d, uint64_t(e) * sizeof(S));
+            }
+        }
+    }
+}
+
+// Single-tensor plans: blockIdx.y = the chunk (the learner it sets out from), blockIdx.x
+// strides over its tiles.
+template <typename T, int MODE>
+__global__ __launch_bounds__(64) void walk_kernel(const uint64_t* table_, int d, unsigned tile_stride) {
+    constexpr int64_t VL = 16 / sizeof(typename Elem<T>::S);
     constexpr int R = MODE == WALK_GATHER ? DDL_WALK_GATHER_ROWS : DDL_WALK_ROWS;
     constexpr int64_t kTileVecs = int64_t(R) * 64;
     const DDL_CONST uint64_t* row = (const DDL_CONST uint64_t*)table_ + size_t(blockIdx.y) * (d + 1);
@@ -708,77 +764,60 @@ __global__ __launch_bounds__(64) void walk_kernel(const uint64_t* table_, int d,
     // rows on absolute 1 KiB boundaries of the chunk at its last position (the owner of a
     // reduced chunk; every learner's copy has the same offset within its buffer)
     const int64_t shift = int64_t((addr[d - 1] % kRowBytes) / 16);
-    const int64_t lane = threadIdx.x;
-    for (int64_t tile = int64_t(blockIdx.x) * kTileVecs - shift; tile <= nv; tile += int64_t(tile_stride) * kTileVecs) {
-        if (tile >= 0 && tile + kTileVecs <= nv) {
-            const uint64_t byte_off = uint64_t(tile + lane) * 16;
-            V acc[R];
-#pragma unroll
-            for (int r = 0; r < R; ++r) acc[r] = stream_load((const DDL_GLOBAL V*)(addr[0] + byte_off) + r * 64);
-            if (MODE != WALK_GATHER) {
-                for (int i0 = 1; i0 < d; i0 += kWalkBatch) {
-                    V x[kWalkBatch][R];
-#pragma unroll
-                    for (int j = 0; j < kWalkBatch; ++j)
-                        if (i0 + j < d) {
-#pragma unroll
-                            for (int r = 0; r < R; ++r)
-                                x[j][r] = stream_load((const DDL_GLOBAL V*)(addr[i0 + j] + byte_off) + r * 64);
-                        }
-#pragma unroll
-                    for (int j = 0; j < kWalkBatch; ++j)
-                        if (i0 + j < d) {
-#pragma unroll
-                            for (int r = 0; r < R; ++r) {
-                                acc[r] = Elem<T>::sum(x[j][r], acc[r]);
-                                if (MODE == WALK_REDUCE)
-                                    stream_store((DDL_GLOBAL V*)(addr[i0 + j] + byte_off) + r * 64, acc[r]);
-                            }
-                        }
-                }
-            }
-            if (MODE != WALK_REDUCE) {
-                for (int i = MODE == WALK_BOTH ? 0 : 1; i < d; ++i) {
-#pragma unroll
-                    for (int r = 0; r < R; ++r) walk_gather_store((DDL_GLOBAL V*)(addr[i] + byte_off) + r * 64, acc[r]);
-                }
-            }
-        } else {
-            // first or last rows of the chunk: per-lane bounds
-            for (int r = 0; r < R; ++r) {
-                const int64_t v = tile + r * 64 + lane;
-                if (v >= 0 && v < nv) {
-                    walk_place<T, V, MODE>(addr, d, uint64_t(v) * 16);
-                } else if (v == nv) {
-                    // the buffer's last, short vector: element by element
-                    for (int64_t e = nv * VL; e < n; ++e) walk_place<T, S, MODE>(addr, d, uint64_t(e) * sizeof(S));
-                }
-            }
-        }
-    }
+    for (int64_t tile = int64_t(blockIdx.x) * kTileVecs - shift; tile <= nv; tile += int64_t(tile_stride) * kTileVecs)
+        walk_tile<T, MODE, R>(addr, d, n, nv, tile, threadIdx.x);
 }
 
-template <typename T>
-hipError_t launch_walk_typed(const ddl_plan& plan, const WalkLevel& level, const uint64_t* d_rows, int mode,
-                             hipStream_t stream) {
+// Several-tensor plans: one workgroup per listed tile (chunk, tile index) of kWalkListRows rows.
+template <typename T, int MODE>
+__global__ __launch_bounds__(64) void walk_kernel_list(const uint64_t* table_, const BlockDesc* __restrict__ items,
+                                                       int d, unsigned block_offset) {
+    constexpr int64_t VL = 16 / sizeof(typename Elem<T>::S);
+    const BlockDesc item = items[blockIdx.x + block_offset];
+    const DDL_CONST uint64_t* row = (const DDL_CONST uint64_t*)table_ + size_t(item.op) * (d + 1);
+    const int64_t n = int64_t(row[0]);
+    const DDL_CONST uint64_t* addr = row + 1;
+    const int64_t nv = n / VL;
+    const int64_t shift = int64_t((addr[d - 1] % kRowBytes) / 16);
+    walk_tile<T, MODE, kWalkListRows>(addr, d, n, nv, int64_t(item.row) * kWalkListRows * 64 - shift, threadIdx.x);
+}
+
+template <typename T, int MODE>
+hipError_t launch_walk_mode(const ddl_plan& plan, const WalkLevel& level, const uint64_t* d_rows,
+                            const BlockDesc* d_items, hipStream_t stream) {
     constexpr uint64_t VL = 16 / sizeof(typename Elem<T>::S);
-    const uint64_t tile_vecs = uint64_t(mode == WALK_GATHER ? DDL_WALK_GATHER_ROWS : DDL_WALK_ROWS) * 64;
+    // the reduce rows list each chunk's positions from the one after its owner to the owner
+    const uint64_t* rows = d_rows + (MODE == WALK_GATHER ? level.gather_rows : level.reduce_rows);
+    if (plan.seg_off.size() > 1) {
+        const uint64_t blocks = MODE == WALK_GATHER ? level.gather_count : level.reduce_count;
+        const BlockDesc* items = d_items + (MODE == WALK_GATHER ? level.gather_items : level.reduce_items);
+        if (blocks > 0xFFFFFFFFull) return hipErrorInvalidValue;
+        const uint64_t per_launch = DDL_LIST_PER_LAUNCH;
+        for (uint64_t start = 0; start < blocks; start += per_launch) {
+            const uint64_t now = blocks - start < per_launch ? blocks - start : per_launch;
+            hipLaunchKernelGGL((walk_kernel_list<T, MODE>), dim3(static_cast<unsigned>(now)), dim3(64), 0, stream,
+                               rows, items, level.d, unsigned(start));
+            const hipError_t err = hipGetLastError();
+            if (err != hipSuccess) return err;
+        }
+        return hipSuccess;
+    }
+    const uint64_t tile_vecs = uint64_t(MODE == WALK_GATHER ? DDL_WALK_GATHER_ROWS : DDL_WALK_ROWS) * 64;
     uint64_t tiles = (level.max_n / VL + 1 + (kRowVecs - 1) + tile_vecs - 1) / tile_vecs;
     const uint64_t max_x = (DDL_MAX_GRID_THREADS / 64 - 1) / uint64_t(plan.P);
     if (tiles > max_x) tiles = max_x;
     if (tiles == 0) tiles = 1;
     const dim3 grid(static_cast<unsigned>(tiles), static_cast<unsigned>(plan.P), 1);
-    // the reduce rows list each chunk's positions from the one after its owner to the owner
-    if (mode == WALK_REDUCE)
-        hipLaunchKernelGGL((walk_kernel<T, WALK_REDUCE>), grid, dim3(64), 0, stream, d_rows + level.reduce_rows,
-                           level.d, grid.x);
-    else if (mode == WALK_BOTH)
-        hipLaunchKernelGGL((walk_kernel<T, WALK_BOTH>), grid, dim3(64), 0, stream, d_rows + level.reduce_rows,
-                           level.d, grid.x);
-    else
-        hipLaunchKernelGGL((walk_kernel<T, WALK_GATHER>), grid, dim3(64), 0, stream, d_rows + level.gather_rows,
-                           level.d, grid.x);
+    hipLaunchKernelGGL((walk_kernel<T, MODE>), grid, dim3(64), 0, stream, rows, level.d, grid.x);
     return hipGetLastError();
+}
+
+template <typename T>
+hipError_t launch_walk_typed(const ddl_plan& plan, const WalkLevel& level, const uint64_t* d_rows,
+                             const BlockDesc* d_items, int mode, hipStream_t stream) {
+    if (mode == WALK_REDUCE) return launch_walk_mode<T, WALK_REDUCE>(plan, level, d_rows, d_items, stream);
+    if (mode == WALK_BOTH) return launch_walk_mode<T, WALK_BOTH>(plan, level, d_rows, d_items, stream);
+    return launch_walk_mode<T, WALK_GATHER>(plan, level, d_rows, d_items, stream);
 }
 
 }  // namespace
@@ -787,7 +826,7 @@ hipError_t launch_resolve_walk(const ddl_plan& plan, const uint64_t* d_walk_plan
                                const PtrTable& table, void* const* d_ptrs, hipStream_t stream) {
     for (const WalkLevel& level : plan.walk_levels)
         for (int half = 0; half < 2; ++half) {
-            const unsigned rows = static_cast<unsigned>(plan.P);
+            const unsigned rows = static_cast<unsigned>(size_t(plan.P) * plan.seg_off.size());
             hipLaunchKernelGGL(resolve_walk, dim3((rows + 255) / 256), dim3(256), 0, stream, table, d_ptrs,
                                d_walk_plan + (half == 0 ? level.reduce_plan : level.gather_plan),
                                d_rows + (half == 0 ? level.reduce_rows : level.gather_rows), rows,
@@ -798,15 +837,15 @@ hipError_t launch_resolve_walk(const ddl_plan& plan, const uint64_t* d_walk_plan
     return hipSuccess;
 }
 
-hipError_t launch_walk(const ddl_plan& plan, const WalkLevel& level, const uint64_t* d_rows, int mode,
-                       hipStream_t stream) {
+hipError_t launch_walk(const ddl_plan& plan, const WalkLevel& level, const uint64_t* d_rows,
+                       const BlockDesc* d_items, int mode, hipStream_t stream) {
     if (level.max_n == 0) return hipSuccess;
     switch (plan.dtype) {
-        case DDL_F32: return launch_walk_typed<float>(plan, level, d_rows, mode, stream);
-        case DDL_F64: return launch_walk_typed<double>(plan, level, d_rows, mode, stream);
-        case DDL_I32: return launch_walk_typed<unsigned>(plan, level, d_rows, mode, stream);
-        case DDL_F16: return launch_walk_typed<_Float16>(plan, level, d_rows, mode, stream);
-        case DDL_BF16: return launch_walk_typed<bf16_bits>(plan, level, d_rows, mode, stream);
+        case DDL_F32: return launch_walk_typed<float>(plan, level, d_rows, d_items, mode, stream);
+        case DDL_F64: return launch_walk_typed<double>(plan, level, d_rows, d_items, mode, stream);
+        case DDL_I32: return launch_walk_typed<unsigned>(plan, level, d_rows, d_items, mode, stream);
+        case DDL_F16: return launch_walk_typed<_Float16>(plan, level, d_rows, d_items, mode, stream);
+        case DDL_BF16: return launch_walk_typed<bf16_bits>(plan, level, d_rows, d_items, mode, stream);
     }
     return hipErrorInvalidValue;
 }

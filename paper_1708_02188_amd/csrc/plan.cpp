@@ -181,30 +181,52 @@ ddl_status_t verify_plan(const ddl_plan& plan) {
         if (at != plan.seg_off[seg] + plan.seg_count[seg]) return DDL_ERR_ARG;
     }
     for (const WalkLevel& lv : plan.walk_levels)
-        for (int half = 0; half < 2; ++half)
-            for (int r = 0; r < P; ++r) {
+        for (int half = 0; half < 2; ++half) {
+            for (size_t r = 0; r < S * size_t(P); ++r) {
                 const uint64_t* row = plan.walk_plan.data() + (half ? lv.gather_plan : lv.reduce_plan) +
-                                      size_t(r) * (size_t(lv.d) + 2);
-                if (row[0] + row[1] > plan.count || row[2] != uint64_t(r)) return DDL_ERR_ARG;
+                                      r * (size_t(lv.d) + 2);
+                const size_t seg = r / P;
+                if (row[0] < plan.seg_off[seg] || row[0] + row[1] > plan.seg_off[seg] + plan.seg_count[seg] ||
+                    row[2] != uint64_t(r % P))
+                    return DDL_ERR_ARG;
                 for (int i = 0; i + 1 < lv.d; ++i) {
                     const int a = int(row[2 + i]);
                     const int pos = (a / stride[lv.dim]) % lv.d;
                     if (int(row[3 + i]) != a + ((pos + 1) % lv.d - pos) * stride[lv.dim]) return DDL_ERR_ARG;
                 }
             }
+            // several tensors: every tile of every non-empty row listed once, in order
+            if (S > 1) {
+                const BlockDesc* item = plan.walk_items.data() + (half ? lv.gather_items : lv.reduce_items);
+                const BlockDesc* end = item + (half ? lv.gather_count : lv.reduce_count);
+                for (size_t r = 0; r < S * size_t(P); ++r) {
+                    const uint64_t n = plan.walk_plan[(half ? lv.gather_plan : lv.reduce_plan) + r * (size_t(lv.d) + 2) + 1];
+                    if (n == 0) continue;
+                    const uint64_t tile_vecs = uint64_t(kWalkListRows) * 64;
+                    const uint64_t tiles = (n / G + 1 + 63 + tile_vecs - 1) / tile_vecs;
+                    for (uint64_t tile = 0; tile < tiles; ++tile, ++item)
+                        if (item >= end || item->op != r || item->row != tile) return DDL_ERR_ARG;
+                }
+                if (item != end) return DDL_ERR_ARG;
+            }
+        }
     return DDL_OK;
 }
 
 void build_walk(ddl_plan* plan) {
     plan->walk_levels.clear();
     plan->walk_plan.clear();
+    plan->walk_items.clear();
     plan->walk_words = 0;
     plan->walk_bytes = 0;
-    if (plan->seg_off.size() != 1 || plan->steps.empty()) return;
+    if (plan->steps.empty()) return;
     const int P = plan->P;
+    const size_t S = plan->seg_off.size();
+    const size_t rows = S * size_t(P);
+    const uint64_t G = 16 / uint64_t(plan->elem_size);
     size_t words = 0;
     for (int d : plan->dims)
-        if (d > 1) words += 2 * size_t(P) * (size_t(d) + 2);
+        if (d > 1) words += 2 * rows * (size_t(d) + 2);
     if (words > kWalkMaxWords) return;
     // first phase of every dimension's reduce-scatter and all-gather in the step list
     std::vector<int> first_reduce(plan->dims.size(), -1), first_gather(plan->dims.size(), -1);
@@ -212,35 +234,47 @@ void build_walk(ddl_plan* plan) {
         const Step& st = plan->steps[s];
         (st.kind == DDL_STEP_REDUCE ? first_reduce : first_gather)[st.dim] = s;
     }
+    int last = -1;
+    for (size_t u = 0; u < plan->dims.size(); ++u)
+        if (plan->dims[u] > 1) last = int(u);
     for (size_t t = 0; t < plan->dims.size(); ++t) {
         const int d = plan->dims[t];
         if (d <= 1) continue;
-        WalkLevel level{int(t), d, 0, 0, 0, 0, 0};
+        WalkLevel level{int(t), d, 0, 0, 0, 0, 0, 0, 0, 0, 0};
         for (int half = 0; half < 2; ++half) {
             const int s0 = half == 0 ? first_reduce[t] : first_gather[t];
             (half == 0 ? level.reduce_plan : level.gather_plan) = plan->walk_plan.size();
             (half == 0 ? level.reduce_rows : level.gather_rows) = plan->walk_words;
-            plan->walk_words += size_t(P) * (size_t(d) + 1);
-            for (int r = 0; r < P; ++r) {
+            (half == 0 ? level.reduce_items : level.gather_items) = plan->walk_items.size();
+            plan->walk_words += rows * (size_t(d) + 1);
+            for (size_t row = 0; row < rows; ++row) {
                 // the chunk that learner r passes on in the dimension's first phase keeps its
                 // range through all d-1 phases; its path is r, next(r), next(next(r)), ...
-                const Op& op0 = plan->ops[size_t(s0) * P + r];
+                const size_t seg = row / P;
+                const Op& op0 = plan->ops[size_t(s0) * rows + row];
                 plan->walk_plan.push_back(op0.off);
                 plan->walk_plan.push_back(op0.n);
-                int at = r;
+                int at = int(row % P);
                 for (int i = 0; i < d; ++i) {
                     plan->walk_plan.push_back(uint64_t(at));
-                    if (i + 1 < d) at = plan->ops[size_t(s0 + i) * P + at].dst;
+                    if (i + 1 < d) at = plan->ops[size_t(s0 + i) * rows + seg * P + at].dst;
                 }
                 if (op0.n > level.max_n) level.max_n = op0.n;
                 // reduce: d reads and d-1 writes of the chunk; gather: 1 read and d-1 writes;
                 // the last dimension of the allreduce does both at once: d reads, d writes
-                int last = -1;
-                for (size_t u = 0; u < plan->dims.size(); ++u)
-                    if (plan->dims[u] > 1) last = int(u);
                 const int accesses = int(t) == last ? (half == 0 ? 2 * d : 0) : (half == 0 ? 2 * d - 1 : d);
                 plan->walk_bytes += op0.n * uint64_t(plan->elem_size) * uint64_t(accesses);
+                if (S > 1 && op0.n > 0) {
+                    // tiles of kWalkListRows rows; one row more than the vectors need, because
+                    // the tiling is shifted onto absolute row boundaries at run time
+                    const uint64_t tile_vecs = uint64_t(kWalkListRows) * 64;
+                    const uint64_t tiles = (op0.n / G + 1 + 63 + tile_vecs - 1) / tile_vecs;
+                    for (uint64_t tile = 0; tile < tiles; ++tile)
+                        plan->walk_items.push_back(BlockDesc{uint32_t(row), uint32_t(tile)});
+                }
             }
+            (half == 0 ? level.reduce_count : level.gather_count) =
+                plan->walk_items.size() - (half == 0 ? level.reduce_items : level.gather_items);
         }
         plan->walk_levels.push_back(level);
     }

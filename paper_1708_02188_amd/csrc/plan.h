@@ -89,20 +89,27 @@ struct Binding {
     uint64_t last_use = 0;
 };
 
-// One box dimension of size d > 1 walked in a single launch (see build_walk): `reduce` / `gather`
-// index the first of P rows in the plan's walk table and in a binding's resolved copy.
+// One box dimension of size d > 1 walked in a single launch (see build_walk): `reduce` /
+// `gather` index the first of S * P rows (tensor-major, then the learner a chunk sets out
+// from) in the plan's walk table and in a binding's resolved copy.  Several-tensor plans
+// also list the tiles of kWalkListRows rows their rows consist of (BlockDesc{row, tile}),
+// since their rows differ in length by orders of magnitude.
+constexpr int kWalkListRows = 4;
 struct WalkLevel {
     int dim;              // 0-based box dimension
     int d;                // ring size
-    uint64_t max_n;       // longest chunk (sizes the launch)
+    uint64_t max_n;       // longest chunk (sizes the launch of a single-tensor plan)
     size_t reduce_plan, gather_plan;   // rows of d + 2 words: element offset, length, the d ring members in order
     size_t reduce_rows, gather_rows;   // rows of d + 1 words: length, then the chunk's d addresses in ring order
+    size_t reduce_items, gather_items; // several-tensor plans: first tile of each half in walk_items,
+    size_t reduce_count, gather_count; // and how many
 };
 
 struct DeviceTables {
     int device = -1;
     Op* ops = nullptr;           // num_steps * P operations, step-major
     uint64_t* walk_plan = nullptr;   // ring-walk rows (learner indices), see WalkLevel
+    BlockDesc* walk_items = nullptr; // ring-walk tiles of a several-tensor plan
     BlockDesc* whole = nullptr;   // work lists of a several-tensor plan
     BlockDesc* ragged = nullptr;
     // step-fused path, created at its first use
@@ -133,6 +140,7 @@ struct ddl_plan {
     uint64_t bytes_total = 0;
     std::vector<ddl::WalkLevel> walk_levels;   // empty: the plan has no ring-walk form
     std::vector<uint64_t> walk_plan;           // rows of all levels (learner indices)
+    std::vector<ddl::BlockDesc> walk_items;    // tiles of all levels, only when S > 1
     size_t walk_words = 0;                     // size of a binding's resolved copy
     uint64_t walk_bytes = 0;                   // memory traffic of the ring-walk form
 
@@ -152,13 +160,13 @@ void split_range(uint64_t lo, uint64_t hi, uint64_t d, uint64_t k, uint64_t G,
 // Fills `plan` (dims, P, count, dtype already validated by the caller).
 void build_schedule(ddl_plan* plan);
 
-// Ring-walk form of a single-tensor plan, derived from its phases (call after build_schedule):
+// Ring-walk form of a plan, derived from its phases (call after build_schedule):
 // the d-1 phases of a dimension's reduce-scatter pass every chunk once round its ring, so one
 // launch can carry each chunk's partial sum from the position after its owner to the owner,
 // storing it at every position on the way exactly as the phases do; likewise the d-1 gather
 // phases copy every completed chunk from its owner to the other d-1 positions.  Leaves the
 // plan without the form if its tables would exceed kWalkMaxWords.
-constexpr size_t kWalkMaxWords = size_t(1) << 22;
+constexpr size_t kWalkMaxWords = size_t(1) << 24;
 void build_walk(ddl_plan* plan);
 
 ddl_status_t validate_dims(const int* dims, int m, int P);

@@ -547,11 +547,12 @@ def test_ring_walk_modes_and_limits(dev):
             assert_bitwise(g, want[j], f"profile mode {mode} learner={j}")
     with pytest.raises(D.DdlError):
         D.ddl_plan_set_walk(plan, 7)
-    tplan = D.ddl_ring_plan_tensors([2, 2], 4, [0, 512], [100, 512], 1024)
+    # a ring too long for the walk tables: 2 * P * (d + 2) words beyond 2^24
+    long_ring = D.ddl_ring_plan([4096], 4096, 64)
     with pytest.raises(D.DdlError) as e:
-        D.ddl_plan_set_walk(tplan, D.DDL_WALK_ON)
+        D.ddl_plan_set_walk(long_ring, D.DDL_WALK_ON)
     assert e.value.status == D.DDL_ERR_UNSUPPORTED
-    assert D.ddl_plan_walk_bytes(tplan) == 0
+    assert D.ddl_plan_walk_bytes(long_ring) == 0
 
 
 def test_capture_with_more_learners_than_the_kernarg_table(dev):
@@ -717,7 +718,10 @@ dims, P = [4, 2], 8
 segments, count = [(0, 64), (64, 100_000), (100_064, 7), (100_072, 1_500_001), (1_600_076, 33)], 1_600_076 + 33
 V = [(rng.uniform(-1, 1, count) * 10.0 ** rng.uniform(-3, 3, count)).astype(np.float32) for _ in range(P)]
 plan = D.ddl_ring_plan_tensors(dims, P, [o for o, _ in segments], [n for _, n in segments], count)
+D.ddl_plan_set_walk(plan, D.DDL_WALK_OFF)
 b = up(V); D.ddl_allreduce_sim(b, P, plan, count); check(b, O.allreduce_tensors(V, dims, segments), "tensor plan, split launches")
+D.ddl_plan_set_walk(plan, D.DDL_WALK_ON)
+b = up(V); D.ddl_allreduce_sim(b, P, plan, count); check(b, O.allreduce_tensors(V, dims, segments), "tensor plan, ring walk, split launches")
 print("stride paths ok")
 """
 
@@ -799,6 +803,7 @@ def test_random_sweep_against_oracle(dev):
                 segments = [(a, int(rng.integers(0, b - a + 1))) for a, b in zip(cuts, cuts[1:] + [count])]
                 plan = D.ddl_ring_plan_tensors(dims, P, [o for o, _ in segments], [n for _, n in segments],
                                                count, dtype)
+                D.ddl_plan_set_walk(plan, D.DDL_WALK_ON if case % 2 else D.DDL_WALK_OFF)
                 D.ddl_allreduce_sim(bufs, P, plan, count, dtype)
                 want = O.allreduce_tensors(V, dims, segments, add=add)
             else:
@@ -853,6 +858,33 @@ def test_tensor_plan_matches_per_tensor_oracle(dev, dims, segments, count):
         assert_bitwise(g, want[j], f"tensor plan all-gather learner={j}")
 
 
+@pytest.mark.parametrize("dims,segments,count", TENSOR_CASES)
+def test_tensor_plan_ring_walk(dev, dims, segments, count):
+    """Several tensors, one launch per dimension: whole buffers after the reduce-scatter, the
+    all-gather and the allreduce equal the phases' (gaps between tensors untouched)."""
+    P = prod(dims)
+    say(f"tensor plan, ring walk dims={dims} tensors={len(segments)} count={count}")
+    rng = np.random.default_rng(700 + count)
+    V = wide_inputs(rng, P, count, D.DDL_F32)
+    plan = D.ddl_ring_plan_tensors(dims, P, [o for o, _ in segments], [n for _, n in segments], count)
+    D.ddl_plan_verify(plan)
+    D.ddl_plan_set_walk(plan, D.DDL_WALK_ON)
+    steps = O.schedule_tensors(dims, segments, 4)
+    want_rs = O._run([v.copy() for v in V], [st for st in steps if st[0] == "RS"])
+    want = O.allreduce_tensors(V, dims, segments)
+    bufs = upload(V, dev)
+    D.ddl_reduce_scatter_sim(bufs, P, plan, count)
+    for j, g in enumerate(download(bufs)):
+        assert_bitwise(g, want_rs[j], f"walk reduce-scatter learner={j}")
+    D.ddl_allgather_sim(bufs, P, plan, count)
+    for j, g in enumerate(download(bufs)):
+        assert_bitwise(g, want[j], f"walk all-gather learner={j}")
+    bufs = upload(V, dev)
+    D.ddl_allreduce_sim(bufs, P, plan, count)
+    for j, g in enumerate(download(bufs)):
+        assert_bitwise(g, want[j], f"walk allreduce learner={j}")
+
+
 def test_tensor_plan_sixteen_bit(dev):
     dims, P = [2, 2], 4
     segments, count = [(0, 24), (24, 808), (832, 9), (848, 70001)], 848 + 70001
@@ -864,6 +896,11 @@ def test_tensor_plan_sixteen_bit(dev):
     want = O.allreduce_tensors(V, dims, segments, add=O.bf16_add)
     for j, g in enumerate(download(bufs, np.uint16)):
         assert_bitwise(g, want[j], f"bf16 tensor plan learner={j}")
+    D.ddl_plan_set_walk(plan, D.DDL_WALK_ON)
+    bufs = upload(V, dev)
+    D.ddl_allreduce_sim(bufs, P, plan, count, D.DDL_BF16)
+    for j, g in enumerate(download(bufs, np.uint16)):
+        assert_bitwise(g, want[j], f"bf16 tensor plan, ring walk learner={j}")
 
 
 # ---------------------------------------------------------------------------------------
@@ -1069,9 +1106,11 @@ def run_config(dev, cfg, fused=True, per_tensor=False):
         shapes = I.resnet50_shapes() if count == I.RESNET50_COUNT else I.resnet101_22k_shapes()
         offs, cnts = I.tensor_segments(shapes)
         tplan = D.ddl_ring_plan_tensors(dims, P, offs, cnts, count)
-        got = device_result(dev, cfg, D.ddl_allreduce_sim, tplan)
-        n = compare_whole({"per-tensor plan": got}, dims, seed, dist, list(zip(offs, cnts)),
-                          f"{cfg['name']} as {len(offs)} tensors")
+        D.ddl_plan_set_walk(tplan, D.DDL_WALK_OFF)
+        got = {"per-tensor plan": device_result(dev, cfg, D.ddl_allreduce_sim, tplan)}
+        D.ddl_plan_set_walk(tplan, D.DDL_WALK_ON)
+        got["per-tensor plan, ring walk"] = device_result(dev, cfg, D.ddl_allreduce_sim, tplan)
+        n = compare_whole(got, dims, seed, dist, list(zip(offs, cnts)), f"{cfg['name']} as {len(offs)} tensors")
         assert n == count
 
 
@@ -1129,7 +1168,10 @@ def test_config5_per_tensor_plan_whole_buffer(dev):
     cfg = I.CONFIGS[4]
     offs, cnts = I.tensor_segments(I.resnet101_22k_shapes())
     tplan = D.ddl_ring_plan_tensors(cfg["dims"], cfg["P"], offs, cnts, cfg["count"])
-    got = device_result(dev, cfg, D.ddl_allreduce_sim, tplan)
-    n = compare_whole({"per-tensor plan": got}, cfg["dims"], cfg["seed"], cfg["dist"], list(zip(offs, cnts)),
+    D.ddl_plan_set_walk(tplan, D.DDL_WALK_OFF)
+    got = {"per-tensor plan": device_result(dev, cfg, D.ddl_allreduce_sim, tplan)}
+    D.ddl_plan_set_walk(tplan, D.DDL_WALK_ON)
+    got["per-tensor plan, ring walk"] = device_result(dev, cfg, D.ddl_allreduce_sim, tplan)
+    n = compare_whole(got, cfg["dims"], cfg["seed"], cfg["dist"], list(zip(offs, cnts)),
                       f"{cfg['name']} as {len(offs)} tensors")
     assert n == cfg["count"]

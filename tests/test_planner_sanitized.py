@@ -61,16 +61,17 @@ static void one(const std::vector<int>& dims, uint64_t count, ddl_dtype_t dtype,
     }
     // ring-walk rows: in bounds, d distinct members of one ring, same range as the phases
     ddl::build_walk(&plan);
-    if (off.size() == 1) {
+    {
         size_t expect = 0;
         for (int d : dims) expect += d > 1;
         if (plan.walk_levels.size() != expect) std::abort();
         uint64_t bytes = 0;
+        const size_t rows = off.size() * (size_t)P;
         for (const ddl::WalkLevel& lv : plan.walk_levels) {
             for (int half = 0; half < 2; ++half)
-                for (int r = 0; r < P; ++r) {
-                    const uint64_t* row = plan.walk_plan.data() + (half ? lv.gather_plan : lv.reduce_plan) + size_t(r) * (lv.d + 2);
-                    if (row[0] + row[1] > count || row[1] > lv.max_n || row[2] != (uint64_t)r) std::abort();
+                for (size_t r = 0; r < rows; ++r) {
+                    const uint64_t* row = plan.walk_plan.data() + (half ? lv.gather_plan : lv.reduce_plan) + r * (lv.d + 2);
+                    if (row[0] + row[1] > count || row[1] > lv.max_n || row[2] != (uint64_t)(r % P)) std::abort();
                     for (int i = 0; i < lv.d; ++i) {
                         if (row[2 + i] >= (uint64_t)P) std::abort();
                         for (int j = 0; j < i; ++j)
@@ -79,11 +80,11 @@ static void one(const std::vector<int>& dims, uint64_t count, ddl_dtype_t dtype,
                     const bool last = &lv == &plan.walk_levels.back();
                     bytes += row[1] * plan.elem_size * (last ? (half ? 0 : 2 * lv.d) : (half ? lv.d : 2 * lv.d - 1));
                 }
+            if (off.size() == 1 && (lv.reduce_count || lv.gather_count)) std::abort();
         }
         if (bytes != plan.walk_bytes || plan.walk_bytes > plan.bytes_total) std::abort();
-        if (plan.walk_words * 8 > (64u << 20)) std::abort();
-    } else if (!plan.walk_levels.empty()) {
-        std::abort();
+        for (const ddl::BlockDesc& it : plan.walk_items)
+            if (it.op >= rows) std::abort();
     }
     // the self-check accepts the plan and trips on planted mistakes
     if (ddl::verify_plan(plan) != DDL_OK) std::abort();
