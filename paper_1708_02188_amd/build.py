@@ -48,15 +48,19 @@ def build_all(out_dir=None, extra_flags=None, verbose=True):
     out_dir = out_dir or os.environ.get("DDLSIM_OUT") or PKG
     extra = list(extra_flags or []) + shlex.split(os.environ.get("DDLSIM_CXXFLAGS", ""))
     os.makedirs(out_dir, exist_ok=True)
-    built = []
-    for lib, (sources, flags) in LIBS.items():
+    def one(item):
+        lib, (sources, flags) = item
         out = os.path.join(out_dir, lib)
         cmd = [hipcc()] + COMMON + flags + extra + ["-o", out] + [os.path.join(CSRC, s) for s in sources]
         if verbose:
             print(" ".join(cmd), flush=True)
         subprocess.run(cmd, check=True)
-        built.append(out)
-    return built
+        return out
+
+    # the libraries are independent: compile them side by side
+    from concurrent.futures import ThreadPoolExecutor
+    with ThreadPoolExecutor(len(LIBS)) as pool:
+        return list(pool.map(one, LIBS.items()))
 
 
 if __name__ == "__main__":
